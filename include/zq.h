@@ -1,0 +1,157 @@
+/*
+ * zq.h -- C ABI of libzq: the quantized linear layer of ZeroQuant
+ * (arXiv 2206.01861) for AMD MI355X (gfx950).
+ *
+ * The layer, in the order a transformer block runs it:
+ *   1. the FP16 hidden state goes through LayerNorm, or bias-add + GeLU, and
+ *      is quantized token by token to INT8 in the same kernel
+ *      (Sec. 4.1 "Token-wise Quantization for Activations"; Sec. 4.3 and
+ *      App. D "Operation Fusion for Token-wise Activation Quantization");
+ *   2. an INT8 x INT8 -> INT32 GeMM runs against weights that were quantized
+ *      offline group by group, to INT8 or to INT4 packed two per byte
+ *      (Sec. 4.1 "Group-wise Quantization for Weights"; Sec. 4.3 INT8 GeMM);
+ *   3. the INT32 accumulator is scaled by the token scale of its row and the
+ *      weight-group scale of its column, bias is added, and FP16 is written
+ *      once (App. D "Dequantization Associated with GeMM Schedule").
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer owned by the caller, valid on the
+ *     current HIP device, 16-byte aligned, and sized as documented.  The
+ *     library allocates nothing, frees nothing and keeps no per-call state.
+ *   - Matrices are dense row-major.  "fp16" is IEEE binary16.
+ *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream)
+ *     and the call returns without synchronising.  Outputs must not alias
+ *     inputs.  Calls sharing a workspace must be ordered on one stream.
+ *   - Arguments are validated on the host before any HIP call; a failed check
+ *     returns an error code and launches nothing.  A failed launch returns
+ *     ZQ_ERR_HIP.
+ *   - Inputs must be finite.  NaN/Inf give unspecified codes, never a fault.
+ *
+ * The quantizer (App. A.2, uniform symmetric): for a block v sharing a scale,
+ *   a = max|v|,  scale = fl32(a / qmax),  inv = fl32(qmax / a),
+ *   code = clamp(round_half_even(fl32(v * inv)), -qmax, +qmax),
+ *   qmax = 2^(bits-1) - 1  (127 or 7);  a == 0 gives codes 0 and scale 0.
+ * The printed S = max(abs(x)) is read as absmax / qmax so that the largest
+ * magnitude maps to +-qmax; the code -2^(bits-1) is never produced.
+ */
+#ifndef ZQ_H
+#define ZQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZQ_OK = 0,
+    ZQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    ZQ_ERR_SHAPE = 2,       /* a dimension is non-positive, not divisible as required, or too large */
+    ZQ_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned */
+    ZQ_ERR_UNSUPPORTED = 4, /* bits / dtype / flag value outside the supported set */
+    ZQ_ERR_HIP = 5          /* the HIP runtime reported an error at launch */
+} zq_status;
+
+typedef void *zq_stream;
+
+/* Largest reduction length accepted: K * 127 * 127 must stay below 2^31. */
+#define ZQ_MAX_K 133143
+
+const char *zq_status_string(zq_status st);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int zq_version(void);
+
+/*
+ * Group-wise weight quantization (Sec. 4.1; quantizer of App. A.2).
+ *   w_fp16   [N,K] fp16, row = output channel.
+ *   groups   g; group j is rows [j*N/g, (j+1)*N/g) over all K columns.
+ *            Requires N % g == 0 and (N/g) % 16 == 0 (a group never straddles
+ *            a matrix-core tile), K % 16 == 0 (K % 32 == 0 for bits = 4).
+ *   bits     8 -> wq_out is int8 [N,K];
+ *            4 -> wq_out is uint8 [N,K/2], byte j of row n =
+ *                 (code[n,2j] & 0xF) | (code[n,2j+1] << 4), two's complement.
+ *   s_w_out  fp32 [g].
+ */
+zq_status zq_quantize_weight_groupwise(const void *w_fp16, int N, int K, int groups, int bits,
+                                       void *wq_out, float *s_w_out, zq_stream stream);
+
+/*
+ * LayerNorm fused with token-wise INT8 quantization (Sec. 4.3; App. D).
+ *   y[m,:] = (x[m,:] - mean) / sqrt(var + eps) * gamma + beta   (fp32, biased variance)
+ *   (xq[m,:], s_tok[m]) = quantizer(y[m,:], qmax 127)
+ *   x_fp16 [M,K]; gamma_fp16 [K]; beta_fp16 [K] or NULL; K % 16 == 0, K <= 32768.
+ *   xq_out int8 [M,K]; s_tok_out fp32 [M].
+ *   y_out  NULL, or [M,K] receiving y before quantization:
+ *          y_dtype 0 = fp16 (rounded), 1 = fp32 (exactly the values quantized).
+ */
+zq_status zq_layernorm_quant_tokenwise(const void *x_fp16, const void *gamma_fp16, const void *beta_fp16,
+                                       float eps, int M, int K, int8_t *xq_out, float *s_tok_out,
+                                       void *y_out, int y_dtype, zq_stream stream);
+
+/*
+ * Bias-add + GeLU fused with token-wise INT8 quantization (Sec. 4.3; App. D).
+ *   y = gelu(h + bias);  approx_tanh 0 = erf form, 1 = tanh approximation.
+ *   h_fp16 [M,N]; bias_fp16 [N] or NULL; N % 16 == 0, N <= 32768.
+ *   Outputs as for the LayerNorm call.
+ */
+zq_status zq_gelu_quant_tokenwise(const void *h_fp16, const void *bias_fp16, int approx_tanh,
+                                  int M, int N, int8_t *xq_out, float *s_tok_out,
+                                  void *y_out, int y_dtype, zq_stream stream);
+
+/*
+ * Bytes of scratch the GeMM calls can use for (M,N,K) with w_bits in {8,4}.
+ * Small-M shapes split the reduction over workgroups and keep INT32 partial
+ * sums there.  0 means no scratch is ever used for that shape.
+ */
+size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
+
+/*
+ * INT8 GeMM with the dequantization epilogue (Sec. 4.3; App. D).
+ *   acc[m,n] = sum_k xq[m,k] * wq[n,k]                          exact, INT32
+ *   out[m,n] = fp16( float(acc) * s_tok[m] * s_w[n / (N/groups)] + bias[n] )
+ *   xq int8 [M,K]; s_tok fp32 [M]; wq int8 [N,K]; s_w fp32 [groups];
+ *   bias_fp16 [N] or NULL; out_fp16 [M,N].
+ *   Requires N % groups == 0, (N/groups) % 16 == 0, K % 16 == 0, K <= ZQ_MAX_K.
+ *   acc_out   NULL, or int32 [M,N] receiving the accumulator (parity tap).
+ *   out_q / out_s_tok  both NULL, or int8 [M,N] / fp32 [M]: the token-wise
+ *             quantization of the FP16-rounded `out`, ready for the next GeMM.
+ *   workspace NULL, or device scratch of workspace_bytes.  With less than
+ *             zq_gemm_workspace_bytes(...) the call still succeeds, on a
+ *             kernel that needs none.
+ */
+zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w,
+                             int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
+                             int32_t *acc_out, int8_t *out_q, float *out_s_tok,
+                             void *workspace, size_t workspace_bytes, zq_stream stream);
+
+/*
+ * Same layer with INT4 weights (the W4/8 policy of Sec. 5 puts INT4 on the
+ * feed-forward weights).  wq4 is uint8 [N,K/2] in the packing documented at
+ * zq_quantize_weight_groupwise; K % 32 == 0.  acc_out holds the product of
+ * the INT8 activation codes with the sign-extended INT4 codes.
+ */
+zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8_t *wq4, const float *s_w,
+                               int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
+                               int32_t *acc_out, int8_t *out_q, float *out_s_tok,
+                               void *workspace, size_t workspace_bytes, zq_stream stream);
+
+/*
+ * Tuning and test hook: force the GeMM schedule instead of choosing it from
+ * the shape (App. D picks a schedule by batch x sequence length).
+ * variant < 0 restores automatic choice.  A forced schedule whose shape
+ * constraints are not met returns ZQ_ERR_UNSUPPORTED from the GeMM call.
+ * Process-wide; not for concurrent use.  Returns the previous value.
+ */
+int zq_debug_force_gemm_variant(int variant);
+
+/* Name of schedule `variant` (NULL when out of range), and the schedule the
+ * dispatcher would choose for a shape. */
+const char *zq_gemm_variant_name(int variant);
+int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZQ_H */

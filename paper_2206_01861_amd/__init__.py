@@ -1,0 +1,21 @@
+"""libzq: ZeroQuant's quantized linear layer (arXiv 2206.01861) for AMD MI355X.
+
+Thin Python binding over the C ABI in include/zq.h.  Every step of the layer
+runs in the HIP kernels of libzq.so; torch only provides device memory and the
+stream.  There is no CPU fallback: a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    ZQError,
+    gemm_choose_variant,
+    gemm_variant_name,
+    gemm_workspace_bytes,
+    force_gemm_variant,
+    lib,
+    lib_path,
+    version,
+    zq_gelu_quant_tokenwise,
+    zq_gemm_i8_dequant,
+    zq_gemm_w4a8_dequant,
+    zq_layernorm_quant_tokenwise,
+    zq_quantize_weight_groupwise,
+)

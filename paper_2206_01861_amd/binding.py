@@ -1,0 +1,199 @@
+"""ctypes binding of libzq.so: argument marshalling only.
+
+Functions carry the names of the C entry points (include/zq.h) and take torch
+CUDA tensors; outputs are allocated here with torch and returned.  The work is
+enqueued on torch's current stream.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libzq.so")
+_lib = None
+
+SYMBOLS = [
+    "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
+    "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
+    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant",
+]
+
+
+class ZQError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libzq error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Load libzq.so (built in-tree by paper_2206_01861_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libzq.so is not built; run `python -m paper_2206_01861_amd.build` "
+                          "(there is no fallback implementation)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    L.zq_status_string.restype = ctypes.c_char_p
+    L.zq_status_string.argtypes = [ci]
+    L.zq_version.restype = ci
+    L.zq_version.argtypes = []
+    L.zq_quantize_weight_groupwise.restype = ci
+    L.zq_quantize_weight_groupwise.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+    L.zq_layernorm_quant_tokenwise.restype = ci
+    L.zq_layernorm_quant_tokenwise.argtypes = [vp, vp, vp, cf, ci, ci, vp, vp, vp, ci, vp]
+    L.zq_gelu_quant_tokenwise.restype = ci
+    L.zq_gelu_quant_tokenwise.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp]
+    L.zq_gemm_workspace_bytes.restype = sz
+    L.zq_gemm_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    gemm_args = [vp, vp, vp, vp, ci, vp, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    L.zq_gemm_i8_dequant.restype = ci
+    L.zq_gemm_i8_dequant.argtypes = gemm_args
+    L.zq_gemm_w4a8_dequant.restype = ci
+    L.zq_gemm_w4a8_dequant.argtypes = gemm_args
+    L.zq_debug_force_gemm_variant.restype = ci
+    L.zq_debug_force_gemm_variant.argtypes = [ci]
+    L.zq_gemm_variant_name.restype = ctypes.c_char_p
+    L.zq_gemm_variant_name.argtypes = [ci]
+    L.zq_gemm_choose_variant.restype = ci
+    L.zq_gemm_choose_variant.argtypes = [ci, ci, ci, ci, sz]
+    _lib = L
+    return L
+
+
+def _check(code):
+    if code != 0:
+        raise ZQError(code, lib().zq_status_string(code).decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtype))
+    return t
+
+
+def version():
+    return lib().zq_version()
+
+
+def gemm_workspace_bytes(M, N, K, w_bits=8):
+    return int(lib().zq_gemm_workspace_bytes(M, N, K, w_bits))
+
+
+def force_gemm_variant(variant):
+    """Force a GeMM schedule (-1 = automatic).  Returns the previous setting."""
+    return lib().zq_debug_force_gemm_variant(int(variant))
+
+
+def gemm_variant_name(variant):
+    s = lib().zq_gemm_variant_name(int(variant))
+    return None if s is None else s.decode()
+
+
+def gemm_choose_variant(M, N, K, w_bits=8, workspace_bytes=0):
+    return lib().zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes)
+
+
+def zq_quantize_weight_groupwise(w_fp16, groups, bits):
+    """w fp16 [N,K] -> (wq int8 [N,K] | uint8 [N,K/2], s_w fp32 [groups])."""
+    _dev(w_fp16, torch.float16, "w_fp16")
+    N, K = w_fp16.shape
+    if bits == 4:
+        wq = torch.empty((N, K // 2), dtype=torch.uint8, device=w_fp16.device)
+    else:
+        wq = torch.empty((N, K), dtype=torch.int8, device=w_fp16.device)
+    s_w = torch.empty(max(groups, 1), dtype=torch.float32, device=w_fp16.device)
+    _check(lib().zq_quantize_weight_groupwise(_ptr(w_fp16), N, K, groups, bits, _ptr(wq), _ptr(s_w), _stream()))
+    return wq, s_w
+
+
+def _y_buf(M, K, y_dtype, device):
+    if y_dtype is None:
+        return None, 0
+    if y_dtype == torch.float32:
+        return torch.empty((M, K), dtype=torch.float32, device=device), 1
+    if y_dtype == torch.float16:
+        return torch.empty((M, K), dtype=torch.float16, device=device), 0
+    raise TypeError("y_dtype must be None, torch.float16 or torch.float32")
+
+
+def zq_layernorm_quant_tokenwise(x_fp16, gamma_fp16, beta_fp16, eps, y_dtype=None, out=None):
+    """x fp16 [M,K] -> (xq int8 [M,K], s_tok fp32 [M], y or None)."""
+    _dev(x_fp16, torch.float16, "x_fp16")
+    _dev(gamma_fp16, torch.float16, "gamma_fp16")
+    if beta_fp16 is not None:
+        _dev(beta_fp16, torch.float16, "beta_fp16")
+    M, K = x_fp16.shape
+    xq, s_tok = out if out is not None else (
+        torch.empty((M, K), dtype=torch.int8, device=x_fp16.device),
+        torch.empty(M, dtype=torch.float32, device=x_fp16.device))
+    y, yd = _y_buf(M, K, y_dtype, x_fp16.device)
+    _check(lib().zq_layernorm_quant_tokenwise(_ptr(x_fp16), _ptr(gamma_fp16), _ptr(beta_fp16), float(eps), M, K,
+                                              _ptr(xq), _ptr(s_tok), _ptr(y), yd, _stream()))
+    return xq, s_tok, y
+
+
+def zq_gelu_quant_tokenwise(h_fp16, bias_fp16=None, approx_tanh=False, y_dtype=None, out=None):
+    """h fp16 [M,N] -> (xq int8 [M,N], s_tok fp32 [M], y or None)."""
+    _dev(h_fp16, torch.float16, "h_fp16")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, N = h_fp16.shape
+    xq, s_tok = out if out is not None else (
+        torch.empty((M, N), dtype=torch.int8, device=h_fp16.device),
+        torch.empty(M, dtype=torch.float32, device=h_fp16.device))
+    y, yd = _y_buf(M, N, y_dtype, h_fp16.device)
+    _check(lib().zq_gelu_quant_tokenwise(_ptr(h_fp16), _ptr(bias_fp16), 1 if approx_tanh else 0, M, N,
+                                         _ptr(xq), _ptr(s_tok), _ptr(y), yd, _stream()))
+    return xq, s_tok, y
+
+
+def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspace, out):
+    _dev(xq, torch.int8, "xq")
+    _dev(s_tok, torch.float32, "s_tok")
+    _dev(wq, wdtype, "wq")
+    _dev(s_w, torch.float32, "s_w")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, K = xq.shape
+    N = wq.shape[0]
+    dev = xq.device
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    out_q = torch.empty((M, N), dtype=torch.int8, device=dev) if requant else None
+    out_s = torch.empty(M, dtype=torch.float32, device=dev) if requant else None
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(fn(_ptr(xq), _ptr(s_tok), _ptr(wq), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N, K, _ptr(out),
+              _ptr(acc), _ptr(out_q), _ptr(out_s), _ptr(workspace), ws_bytes, _stream()))
+    return out, acc, out_q, out_s
+
+
+def zq_gemm_i8_dequant(xq, s_tok, wq, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,
+                       out=None):
+    """-> (out fp16 [M,N], acc int32 | None, out_q int8 | None, out_s_tok fp32 | None)."""
+    return _gemm(lib().zq_gemm_i8_dequant, torch.int8, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant,
+                 workspace, out)
+
+
+def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,
+                         out=None):
+    """INT4-packed weights uint8 [N,K/2]; otherwise as zq_gemm_i8_dequant."""
+    if wq4.shape[1] * 2 != xq.shape[1]:
+        raise ValueError("wq4 must be [N, K/2]")
+    return _gemm(lib().zq_gemm_w4a8_dequant, torch.uint8, xq, s_tok, wq4, s_w, bias_fp16, want_acc, requant,
+                 workspace, out)

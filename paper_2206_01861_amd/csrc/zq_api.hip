@@ -1,0 +1,159 @@
+// C ABI of libzq: argument validation and dispatch.  Every check runs on the
+// host before any HIP call, so a bad argument launches nothing.
+#include "../../include/zq.h"
+#include "zq_internal.h"
+
+#include <atomic>
+
+namespace {
+
+std::atomic<int> g_forced_variant{-1};
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+constexpr int kMaxRow = 32768;   // longest row the fused front-ends keep in registers
+
+zq_status check_rowquant(const void *in, const void *p0, const void *p1, int M, int K, const int8_t *xq,
+                         const float *s_tok, const void *y_out, int y_dtype) {
+    if (in == nullptr || xq == nullptr || s_tok == nullptr) return ZQ_ERR_NULL;
+    if (M <= 0 || K <= 0 || (K % 16) != 0 || K > kMaxRow) return ZQ_ERR_SHAPE;
+    if (y_dtype != 0 && y_dtype != 1) return ZQ_ERR_UNSUPPORTED;
+    if (misaligned(in) || misaligned(p0) || misaligned(p1) || misaligned(xq) || misaligned(s_tok) ||
+        misaligned(y_out))
+        return ZQ_ERR_ALIGN;
+    return ZQ_OK;
+}
+
+zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, const float *s_w, int groups,
+                      const void *bias, int M, int N, int K, void *out, int32_t *acc_out, int8_t *out_q,
+                      float *out_s_tok, void *workspace, size_t workspace_bytes, int w_bits, zq_stream stream) {
+    if (xq == nullptr || s_tok == nullptr || wq == nullptr || s_w == nullptr || out == nullptr) return ZQ_ERR_NULL;
+    if ((out_q == nullptr) != (out_s_tok == nullptr)) return ZQ_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
+    if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
+    if ((K % (w_bits == 4 ? 32 : 16)) != 0 || K > ZQ_MAX_K) return ZQ_ERR_SHAPE;
+    if (out_q != nullptr && N > kMaxRow) return ZQ_ERR_SHAPE;
+    if (misaligned(xq) || misaligned(s_tok) || misaligned(wq) || misaligned(s_w) || misaligned(bias) ||
+        misaligned(out) || misaligned(acc_out) || misaligned(out_q) || misaligned(out_s_tok) ||
+        misaligned(workspace))
+        return ZQ_ERR_ALIGN;
+    if (workspace == nullptr) workspace_bytes = 0;
+
+    int variant = g_forced_variant.load();
+    if (variant >= 0) {
+        if (!zq::gemm_variant_supports(variant, M, N, K, w_bits, workspace_bytes)) return ZQ_ERR_UNSUPPORTED;
+    } else {
+        variant = zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes);
+    }
+    zq::GemmArgs a;
+    a.xq = xq; a.s_tok = s_tok; a.wq = wq; a.s_w = s_w; a.groups = groups; a.bias = bias;
+    a.M = M; a.N = N; a.K = K; a.out = out; a.acc_out = acc_out;
+    a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.w_bits = w_bits;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (zq::launch_gemm(variant, a, st) != hipSuccess) return ZQ_ERR_HIP;
+    if (out_q != nullptr) {
+        // Re-quantization for the next GeMM: token-wise quantizer over the FP16 row just written.
+        if (zq::launch_rowquant(zq::kOpIdentity, out, nullptr, nullptr, 0.0f, M, N, out_q, out_s_tok, nullptr, 0,
+                                st) != hipSuccess)
+            return ZQ_ERR_HIP;
+    }
+    return ZQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *zq_status_string(zq_status st) {
+    switch (st) {
+        case ZQ_OK: return "ok";
+        case ZQ_ERR_NULL: return "a required pointer is NULL";
+        case ZQ_ERR_SHAPE: return "bad shape: non-positive, not divisible as required, or too large";
+        case ZQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case ZQ_ERR_UNSUPPORTED: return "unsupported bits, dtype, flag or forced schedule";
+        case ZQ_ERR_HIP: return "the HIP runtime reported an error";
+    }
+    return "unknown status";
+}
+
+int zq_version(void) { return 100; }
+
+zq_status zq_quantize_weight_groupwise(const void *w_fp16, int N, int K, int groups, int bits, void *wq_out,
+                                       float *s_w_out, zq_stream stream) {
+    if (w_fp16 == nullptr || wq_out == nullptr || s_w_out == nullptr) return ZQ_ERR_NULL;
+    if (bits != 8 && bits != 4) return ZQ_ERR_UNSUPPORTED;
+    if (N <= 0 || K <= 0 || groups <= 0 || groups > 65535) return ZQ_ERR_SHAPE;
+    if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
+    if ((K % (bits == 4 ? 32 : 16)) != 0) return ZQ_ERR_SHAPE;
+    if (misaligned(w_fp16) || misaligned(wq_out) || misaligned(s_w_out)) return ZQ_ERR_ALIGN;
+    hipError_t e = zq::launch_weight_quant(w_fp16, N, K, groups, bits, wq_out, s_w_out,
+                                           reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
+zq_status zq_layernorm_quant_tokenwise(const void *x_fp16, const void *gamma_fp16, const void *beta_fp16, float eps,
+                                       int M, int K, int8_t *xq_out, float *s_tok_out, void *y_out, int y_dtype,
+                                       zq_stream stream) {
+    if (gamma_fp16 == nullptr) return ZQ_ERR_NULL;
+    zq_status s = check_rowquant(x_fp16, gamma_fp16, beta_fp16, M, K, xq_out, s_tok_out, y_out, y_dtype);
+    if (s != ZQ_OK) return s;
+    if (!(eps >= 0.0f)) return ZQ_ERR_UNSUPPORTED;
+    hipError_t e = zq::launch_rowquant(zq::kOpLayerNorm, x_fp16, gamma_fp16, beta_fp16, eps, M, K, xq_out, s_tok_out,
+                                       y_out, y_dtype, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
+zq_status zq_gelu_quant_tokenwise(const void *h_fp16, const void *bias_fp16, int approx_tanh, int M, int N,
+                                  int8_t *xq_out, float *s_tok_out, void *y_out, int y_dtype, zq_stream stream) {
+    zq_status s = check_rowquant(h_fp16, bias_fp16, nullptr, M, N, xq_out, s_tok_out, y_out, y_dtype);
+    if (s != ZQ_OK) return s;
+    if (approx_tanh != 0 && approx_tanh != 1) return ZQ_ERR_UNSUPPORTED;
+    hipError_t e = zq::launch_rowquant(approx_tanh ? zq::kOpGeluTanh : zq::kOpGeluErf, h_fp16, bias_fp16, nullptr,
+                                       0.0f, M, N, xq_out, s_tok_out, y_out, y_dtype,
+                                       reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
+size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits) {
+    if (M <= 0 || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return 0;
+    size_t best = 0;
+    for (int v = 0; v < zq::kGemmVariantCount; ++v) {
+        size_t need = zq::gemm_variant_workspace(v, M, N, K, w_bits);
+        if (need > best && zq::gemm_variant_supports(v, M, N, K, w_bits, need)) best = need;
+    }
+    return best;
+}
+
+zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w, int groups,
+                             const void *bias_fp16, int M, int N, int K, void *out_fp16, int32_t *acc_out,
+                             int8_t *out_q, float *out_s_tok, void *workspace, size_t workspace_bytes,
+                             zq_stream stream) {
+    return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
+                       workspace, workspace_bytes, 8, stream);
+}
+
+zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8_t *wq4, const float *s_w,
+                               int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
+                               int32_t *acc_out, int8_t *out_q, float *out_s_tok, void *workspace,
+                               size_t workspace_bytes, zq_stream stream) {
+    return gemm_common(xq, s_tok, wq4, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
+                       workspace, workspace_bytes, 4, stream);
+}
+
+int zq_debug_force_gemm_variant(int variant) {
+    if (variant >= zq::kGemmVariantCount) variant = -1;
+    return g_forced_variant.exchange(variant < 0 ? -1 : variant);
+}
+
+const char *zq_gemm_variant_name(int variant) {
+    switch (variant) {
+        case zq::kGemmSimple: return "simple";
+        case zq::kGemmTile128: return "tile128";
+        case zq::kGemmTile256: return "tile256";
+        case zq::kGemmSkinny: return "skinny";
+        case zq::kGemmSkinnySplitK: return "skinny_splitk";
+    }
+    return nullptr;
+}
+
+}  // extern "C"

@@ -1,0 +1,64 @@
+// Schedule selection for the GeMM calls (App. D: the schedule is chosen at run
+// time from batch x sequence length so that padding is lowest; large token
+// counts are ranked by matrix-core throughput, small ones by memory bandwidth).
+#include "../../include/zq.h"
+#include "zq_internal.h"
+
+namespace zq {
+
+hipError_t launch_gemm_simple(const GemmArgs &a, hipStream_t st);
+hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st);
+hipError_t launch_gemm_skinny(const GemmArgs &a, bool split_k, hipStream_t st);
+int skinny_splits(int N, int K, int w_bits);
+
+size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits) {
+    if (variant != kGemmSkinnySplitK) return 0;
+    const int splits = skinny_splits(N, K, w_bits);
+    if (splits <= 1) return 0;
+    return (size_t)splits * (size_t)M * (size_t)N * sizeof(int32_t);
+}
+
+bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes) {
+    switch (variant) {
+        case kGemmSimple:
+            return true;
+        case kGemmTile128:
+        case kGemmTile256:
+            return (K % 128) == 0;
+        case kGemmSkinny:
+            return M <= 64 && (K % (w_bits == 8 ? 128 : 256)) == 0;
+        case kGemmSkinnySplitK:
+            return M <= 64 && (K % (w_bits == 8 ? 128 : 256)) == 0 &&
+                   workspace_bytes >= gemm_variant_workspace(variant, M, N, K, w_bits);
+    }
+    return false;
+}
+
+hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st) {
+    switch (variant) {
+        case kGemmSimple: return launch_gemm_simple(a, st);
+        case kGemmTile128: return launch_gemm_tile(a, 128, st);
+        case kGemmTile256: return launch_gemm_tile(a, 256, st);
+        case kGemmSkinny: return launch_gemm_skinny(a, false, st);
+        case kGemmSkinnySplitK: return launch_gemm_skinny(a, true, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace zq
+
+extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes) {
+    using namespace zq;
+    if (M <= 64) {
+        if (gemm_variant_supports(kGemmSkinnySplitK, M, N, K, w_bits, workspace_bytes) &&
+            gemm_variant_workspace(kGemmSkinnySplitK, M, N, K, w_bits) > 0)
+            return kGemmSkinnySplitK;
+        if (gemm_variant_supports(kGemmSkinny, M, N, K, w_bits, 0)) return kGemmSkinny;
+        return kGemmSimple;
+    }
+    if ((K % 128) != 0) return kGemmSimple;
+    // 256x256 tiles once they fill the chip; 128x128 tiles waste less on ragged or small problems.
+    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    if (t256 >= 256) return kGemmTile256;
+    return kGemmTile128;
+}

@@ -1,0 +1,48 @@
+// Host-side launcher declarations shared between the libzq translation units.
+// Every launcher assumes its arguments were validated by the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace zq {
+
+enum RowOp { kOpLayerNorm = 0, kOpGeluErf = 1, kOpGeluTanh = 2, kOpIdentity = 3 };
+
+// in fp16 [M,K]; p0 = gamma (LayerNorm) or bias (GeLU, nullable); p1 = beta (nullable).
+hipError_t launch_rowquant(RowOp op, const void *in, const void *p0, const void *p1, float eps, int M, int K,
+                           int8_t *xq, float *s_tok, void *y_out, int y_dtype, hipStream_t st);
+
+hipError_t launch_weight_quant(const void *w, int N, int K, int groups, int bits, void *wq, float *s_w,
+                               hipStream_t st);
+
+// GeMM schedules.  The order is part of the test/tuning hook of the C ABI.
+enum GemmVariant {
+    kGemmSimple = 0,      // one wave per 16x16 tile, operands from global; any legal shape
+    kGemmTile128 = 1,     // 128x128 block tile, LDS staged
+    kGemmTile256 = 2,     // 256x256 block tile, LDS staged
+    kGemmSkinny = 3,      // M <= 64: weight streaming, reduction split inside the workgroup
+    kGemmSkinnySplitK = 4,// M <= 64: reduction also split across workgroups (needs workspace)
+    kGemmVariantCount = 5
+};
+
+struct GemmArgs {
+    const int8_t *xq;
+    const float *s_tok;
+    const void *wq;       // int8 [N,K] or packed uint8 [N,K/2]
+    const float *s_w;
+    int groups;
+    const void *bias;     // fp16 [N] or null
+    int M, N, K;
+    void *out;            // fp16 [M,N]
+    int32_t *acc_out;     // nullable
+    void *workspace;
+    size_t workspace_bytes;
+    int w_bits;           // 8 or 4
+};
+
+bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
+size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);
+hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st);
+
+}  // namespace zq

@@ -1,0 +1,114 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every
+symbol the header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2206_01861_amd as zq
+from paper_2206_01861_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x10000  # a non-NULL, 16-byte aligned fake device address; never dereferenced on an error path
+OK, E_NULL, E_SHAPE, E_ALIGN, E_UNSUP = 0, 1, 2, 3, 4
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "zq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = zq.lib()
+    names = _declared()
+    assert "zq_gemm_i8_dequant" in names and "zq_quantize_weight_groupwise" in names
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(binding.SYMBOLS)
+
+
+def test_status_strings_and_version():
+    L = zq.lib()
+    assert zq.version() >= 100
+    seen = set()
+    for code in range(6):
+        s = L.zq_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+
+
+def test_variant_table():
+    names = [zq.gemm_variant_name(i) for i in range(8)]
+    assert names[0] == "simple" and None in names
+    # decode shapes go to a weight-streaming schedule, prefill shapes to a tiled one
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(1, 6144, 2048)).startswith("skinny")
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 4096, 1024)).startswith("tile")
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(128, 768, 784)) == "simple"   # K not a multiple of 128
+    ws = zq.gemm_workspace_bytes(64, 6144, 24576)
+    assert ws > 0 and ws % (64 * 6144 * 4) == 0
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws)) == "skinny_splitk"
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws - 1)) == "skinny"
+    assert zq.gemm_workspace_bytes(4096, 4096, 1024) == 0
+
+
+def test_weight_quant_validation():
+    f = zq.lib().zq_quantize_weight_groupwise
+    assert f(None, 64, 64, 4, 8, P, P, None) == E_NULL
+    assert f(P, 64, 64, 4, 8, None, P, None) == E_NULL
+    assert f(P, 64, 64, 4, 5, P, P, None) == E_UNSUP
+    assert f(P, 0, 64, 4, 8, P, P, None) == E_SHAPE
+    assert f(P, 64, 64, 3, 8, P, P, None) == E_SHAPE        # N % g
+    assert f(P, 64, 64, 8, 8, P, P, None) == E_SHAPE        # group of 8 rows
+    assert f(P, 64, 40, 4, 8, P, P, None) == E_SHAPE        # K % 16
+    assert f(P, 64, 48, 4, 4, P, P, None) == E_SHAPE        # K % 32 for INT4
+    assert f(P + 4, 64, 64, 4, 8, P, P, None) == E_ALIGN
+
+
+def test_rowquant_validation():
+    ln = zq.lib().zq_layernorm_quant_tokenwise
+    ge = zq.lib().zq_gelu_quant_tokenwise
+    assert ln(None, P, P, 1e-5, 4, 64, P, P, None, 0, None) == E_NULL
+    assert ln(P, None, P, 1e-5, 4, 64, P, P, None, 0, None) == E_NULL      # gamma is required
+    assert ln(P, P, None, 1e-5, 4, 60, P, P, None, 0, None) == E_SHAPE
+    assert ln(P, P, None, 1e-5, 0, 64, P, P, None, 0, None) == E_SHAPE
+    assert ln(P, P, None, 1e-5, 4, 65536, P, P, None, 0, None) == E_SHAPE
+    assert ln(P, P, None, 1e-5, 4, 64, P, P, P, 2, None) == E_UNSUP
+    assert ln(P, P, None, -1.0, 4, 64, P, P, None, 0, None) == E_UNSUP
+    assert ln(P, P, None, 1e-5, 4, 64, P + 8, P, None, 0, None) == E_ALIGN
+    assert ge(P, None, 0, 4, 64, None, P, None, 0, None) == E_NULL
+    assert ge(P, None, 2, 4, 64, P, P, None, 0, None) == E_UNSUP
+    assert ge(P, None, 0, 4, 72, P, P, None, 0, None) == E_SHAPE
+
+
+@pytest.mark.parametrize("fname,kmul", [("zq_gemm_i8_dequant", 16), ("zq_gemm_w4a8_dequant", 32)])
+def test_gemm_validation(fname, kmul):
+    f = getattr(zq.lib(), fname)
+
+    def call(xq=P, s_tok=P, wq=P, s_w=P, groups=4, bias=None, M=8, N=64, K=128, out=P, acc=None,
+             out_q=None, out_s=None, ws=None, ws_bytes=0):
+        return f(xq, s_tok, wq, s_w, groups, bias, M, N, K, out, acc, out_q, out_s, ws, ws_bytes, None)
+
+    assert call(xq=None) == E_NULL
+    assert call(out=None) == E_NULL
+    assert call(out_q=P) == E_NULL                 # re-quantization outputs come as a pair
+    assert call(M=0) == E_SHAPE
+    assert call(groups=3) == E_SHAPE
+    assert call(groups=8) == E_SHAPE               # 8 columns per group
+    assert call(K=128 + kmul // 2) == E_SHAPE
+    assert call(K=133152) == E_SHAPE               # INT32 accumulator could wrap
+    assert call(bias=P + 2) == E_ALIGN
+    prev = zq.force_gemm_variant(2)
+    try:
+        assert call(K=kmul * 3) == E_UNSUP         # forced tiled schedule cannot take this K
+    finally:
+        zq.force_gemm_variant(prev)
+    assert zq.force_gemm_variant(-1) == -1
+
+
+def test_missing_library_is_an_error(tmp_path, monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))
+    with pytest.raises(ImportError):
+        binding.lib()

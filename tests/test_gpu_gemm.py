@@ -1,0 +1,223 @@
+"""GPU parity: the INT8 / W4A8 GeMM with its dequantization epilogue against
+the CPU oracle, for every schedule, through the C ABI.  Integer results are
+compared bit for bit, FP16 outputs within 2e-3 of the fp64 reference."""
+import numpy as np
+import pytest
+import torch
+
+import zq_inputs
+from helpers import assert_bit_equal, assert_out_close, dev, freivalds_gpu, host
+
+pytestmark = pytest.mark.gpu
+
+SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK = range(5)
+
+
+@pytest.fixture(scope="module")
+def zq():
+    import paper_2206_01861_amd as lib
+    lib.lib()
+    return lib
+
+
+@pytest.fixture(scope="module")
+def orc():
+    from oracle import zq_oracle
+    return zq_oracle
+
+
+def _case(rng, M, N, K, g, bits):
+    xq = zq_inputs.random_codes(rng, (M, K))
+    xq[:, 0] = 127
+    s_tok = zq_inputs.random_scales(rng, M, 5e-3, 0.3)
+    s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-3)
+    bias = zq_inputs.bias(rng, N, std=0.05)
+    codes = zq_inputs.random_codes(rng, (N, K), qmax=127 if bits == 8 else 7)
+    if bits == 8:
+        wq = codes
+    else:
+        u = codes.astype(np.uint8) & 0xF
+        wq = (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+    return xq, s_tok, s_w, bias, codes, wq
+
+
+def _run(zq, bits, variant, xq, s_tok, wq, s_w, bias, workspace=None, requant=False):
+    fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
+    prev = zq.force_gemm_variant(variant)
+    try:
+        res = fn(dev(xq), dev(s_tok), dev(wq), dev(s_w), None if bias is None else dev(bias),
+                 want_acc=True, requant=requant, workspace=workspace)
+        torch.cuda.synchronize()
+    finally:
+        zq.force_gemm_variant(prev)
+    return res
+
+
+def _check(orc, res, xq, s_tok, codes, s_w, bias, what):
+    out, acc = host(res[0]), host(res[1])
+    acc_o = orc.matmul_i32(xq, codes)
+    assert_bit_equal(acc, acc_o, what + " acc")
+    ref, mag = orc.dequant(acc_o, s_tok, s_w, bias)
+    assert_out_close(out, ref, mag, what + " out")
+
+
+# (variant, M, N, K, groups): several tiles in each direction plus ragged tails
+SHAPES = [
+    (SIMPLE, 1, 16, 16, 1), (SIMPLE, 7, 48, 80, 3), (SIMPLE, 17, 768, 784, 48), (SIMPLE, 129, 96, 1024, 2),
+    (TILE128, 128, 768, 768, 48), (TILE128, 129, 272, 256, 17), (TILE128, 300, 400, 384, 25),
+    (TILE128, 1, 16, 128, 1), (TILE128, 515, 1024, 1024, 64),
+    (TILE256, 256, 256, 128, 16), (TILE256, 300, 528, 512, 33), (TILE256, 1030, 768, 256, 48),
+    (TILE256, 17, 16, 384, 1),
+    (SKINNY, 1, 64, 128, 4), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
+    (SKINNY, 16, 208, 1280, 13), (SKINNY, 17, 80, 512, 5), (SKINNY, 32, 2048, 2048, 128),
+    (SKINNY, 33, 144, 896, 9), (SKINNY, 64, 1024, 1536, 64), (SKINNY, 50, 16, 256, 1),
+    (SKINNY_SPLITK, 1, 2048, 8192, 128), (SKINNY_SPLITK, 8, 256, 4096, 16), (SKINNY_SPLITK, 32, 2048, 8192, 128),
+    (SKINNY_SPLITK, 64, 1024, 6144, 64), (SKINNY_SPLITK, 13, 80, 2304, 5),
+]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("variant,M,N,K,g", SHAPES)
+def test_gemm_against_oracle(zq, orc, bits, variant, M, N, K, g):
+    print("gemm", zq.gemm_variant_name(variant), bits, M, N, K, g, flush=True)
+    if bits == 4 and K % 32:
+        pytest.skip("INT4 needs K % 32 == 0")
+    if bits == 4 and variant in (SKINNY, SKINNY_SPLITK) and K % 256:
+        pytest.skip("INT4 streaming schedule steps K by 256")
+    rng = zq_inputs.rng_for(4, variant * 1000 + M + N + K + bits)
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
+    ws = None
+    if variant == SKINNY_SPLITK:
+        nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+        if nbytes == 0:
+            pytest.skip("shape does not split")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    res = _run(zq, bits, variant, xq, s_tok, wq, s_w, bias, workspace=ws)
+    _check(orc, res, xq, s_tok, codes, s_w, bias, "%s %d-bit %dx%dx%d" % (zq.gemm_variant_name(variant), bits, M, N, K))
+
+
+def test_no_bias_and_extreme_codes(zq, orc):
+    # all codes at +-127 with K at the largest workload value: |acc| = 127*127*K, no wrap
+    M, N, K, g = 20, 32, 24576, 2
+    xq = np.full((M, K), 127, np.int8)
+    wq = np.full((N, K), 127, np.int8)
+    wq[1::2] = -127
+    s_tok = np.full(M, 1e-3, np.float32)
+    s_w = np.full(g, 1e-4, np.float32)
+    for variant in (SIMPLE, TILE128, SKINNY):
+        res = _run(zq, 8, variant, xq, s_tok, wq, s_w, None)
+        acc = host(res[1])
+        assert (acc[:, 0::2] == 16129 * K).all() and (acc[:, 1::2] == -16129 * K).all()
+        _check(orc, res, xq, s_tok, wq, s_w, None, "extreme")
+
+
+def test_requant_epilogue(zq, orc):
+    rng = zq_inputs.rng_for(4, 77)
+    M, N, K, g = 37, 256, 512, 16
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+    out, acc, out_q, out_s = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias, requant=True)
+    # token-wise quantizer over the FP16 tensor the GeMM wrote: bit-exact
+    q_o, s_o = orc.quant_tokenwise(host(out).astype(np.float32))
+    assert_bit_equal(host(out_s), s_o, "out_s_tok")
+    assert_bit_equal(host(out_q), q_o, "out_q")
+
+
+def test_dispatch_and_determinism(zq, orc):
+    rng = zq_inputs.rng_for(4, 78)
+    for (M, N, K, g) in [(128, 768, 768, 48), (8, 2048, 2048, 128), (200, 512, 144, 32)]:
+        xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+        nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        r1 = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
+        r2 = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
+        _check(orc, r1, xq, s_tok, codes, s_w, bias, "auto %dx%dx%d" % (M, N, K))
+        assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1])
+
+
+def test_quantized_linear_end_to_end(zq, orc):
+    """LayerNorm+quant -> GeMM -> GeLU+quant -> GeMM on BERT-large FFC shapes (fewer tokens),
+    every stage checked against the oracle fed with the previous GPU stage."""
+    rng = zq_inputs.rng_for(2, 5)
+    M, H, F, g = 256, 1024, 4096, 64
+    x = zq_inputs.config_activations("c2", rng, M, H)
+    gamma, beta = zq_inputs.layernorm_params(rng, H)
+    w1, b1 = zq_inputs.weights(rng, F, H), zq_inputs.bias(rng, F)
+    w2, b2 = zq_inputs.weights(rng, H, F), zq_inputs.bias(rng, H)
+    wq1, sw1 = zq.zq_quantize_weight_groupwise(dev(w1), g, 8)
+    wq2, sw2 = zq.zq_quantize_weight_groupwise(dev(w2), g, 8)
+    xq, st, _ = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), dev(beta), 1e-5)
+    h, acc1, _, _ = zq.zq_gemm_i8_dequant(xq, st, wq1, sw1, dev(b1), want_acc=True)
+    hq, st2, y2 = zq.zq_gelu_quant_tokenwise(h, None, y_dtype=torch.float32)
+    o, acc2, _, _ = zq.zq_gemm_i8_dequant(hq, st2, wq2, sw2, dev(b2), want_acc=True)
+    torch.cuda.synchronize()
+    a1 = orc.matmul_i32(host(xq), host(wq1))
+    assert_bit_equal(host(acc1), a1, "acc1")
+    ref1, mag1 = orc.dequant(a1, host(st), host(sw1), b1)
+    assert_out_close(host(h), ref1, mag1, "h")
+    q_o, s_o = orc.quant_tokenwise(host(y2))
+    assert_bit_equal(host(hq), q_o, "hq")
+    assert_bit_equal(host(st2), s_o, "st2")
+    a2 = orc.matmul_i32(host(hq), host(wq2))
+    assert_bit_equal(host(acc2), a2, "acc2")
+    ref2, mag2 = orc.dequant(a2, host(st2), host(sw2), b2)
+    assert_out_close(host(o), ref2, mag2, "o")
+    # and the quantized layer tracks the fp64 layer it replaces
+    y64, _ = orc.layernorm(x, gamma, beta, 1e-5)
+    h64 = y64 @ w1.astype(np.float64).T + b1.astype(np.float64)
+    g64 = 0.5 * h64 * (1 + np.vectorize(__import__("math").erf)(h64 / np.sqrt(2)))
+    o64 = g64 @ w2.astype(np.float64).T + b2.astype(np.float64)
+    rel = np.linalg.norm(host(o).astype(np.float64) - o64) / np.linalg.norm(o64)
+    print("end-to-end relative error vs fp64 layer: %.4f" % rel, flush=True)
+    assert rel < 0.05
+
+
+# Full-size workloads: sampled rows against the oracle plus the Freivalds identity on everything.
+FULL = [
+    ("c2_ffc1", 4096), ("c2_ffc2", 4096), ("c3_qkv", 2048), ("c3_ffc2", 32), ("c3_ffc1", 1),
+    ("c4_ffc1", 16), ("c4_ffc2", 1), ("c4_ffc1", 4096), ("c4_qkv", 16), ("c5_ffc2", 64), ("c5_qkv", 64),
+    ("c5_ffc1", 16384),
+]
+
+
+@pytest.mark.parametrize("name,M", FULL)
+def test_full_size_workloads(zq, orc, name, M):
+    print("full", name, M, flush=True)
+    K, N, g, bits = zq_inputs.LINEARS[name]
+    rng = zq_inputs.rng_for(int(name[1]), M)
+    g_t = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED + M)
+    qmax = 127 if bits == 8 else 7
+    xq_t = torch.randint(-127, 128, (M, K), generator=g_t, device="cuda", dtype=torch.int8)
+    codes_t = torch.randint(-qmax, qmax + 1, (N, K), generator=g_t, device="cuda", dtype=torch.int8)
+    if bits == 8:
+        wq_t = codes_t
+    else:
+        u = codes_t.to(torch.uint8) & 0xF
+        wq_t = (u[:, 0::2] | (u[:, 1::2] << 4)).contiguous()
+    s_tok = zq_inputs.random_scales(rng, M, 5e-3, 0.3)
+    s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-3)
+    bias = zq_inputs.bias(rng, N, std=0.05)
+    nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
+    out, acc, _, _ = fn(xq_t, dev(s_tok), wq_t, dev(s_w), dev(bias), want_acc=True, workspace=ws)
+    torch.cuda.synchronize()
+    freivalds_gpu(acc, xq_t, codes_t, seed=M + N)
+    rows = np.unique(np.concatenate([[0, M - 1, M // 2], rng.integers(0, M, size=5),
+                                     [min(M - 1, 255), min(M - 1, 256), min(M - 1, 127)]]))
+    xq_h, codes_h = host(xq_t[torch.from_numpy(rows).cuda()]), host(codes_t)
+    acc_o = orc.matmul_i32(xq_h, codes_h)
+    acc_rows = host(acc[torch.from_numpy(rows).cuda()])
+    assert_bit_equal(acc_rows, acc_o, name + " acc rows")
+    ref, mag = orc.dequant(acc_o, s_tok[rows], s_w, bias)
+    assert_out_close(host(out[torch.from_numpy(rows).cuda()]), ref, mag, name + " out rows")
+    # the FP16 output must be the epilogue of the accumulator everywhere (library ops, fp64)
+    gs = N // g
+    step = max(1, (1 << 26) // N)
+    sw_cols = torch.from_numpy(np.repeat(s_w.astype(np.float64), gs)).cuda()
+    b64 = torch.from_numpy(bias.astype(np.float64)).cuda()
+    st64 = torch.from_numpy(s_tok.astype(np.float64)).cuda()
+    for m0 in range(0, M, step):
+        p = acc[m0:m0 + step].to(torch.float64) * st64[m0:m0 + step, None] * sw_cols[None, :]
+        err = (out[m0:m0 + step].to(torch.float64) - (p + b64[None, :])).abs()
+        tol = 2e-3 * (p.abs() + b64.abs()[None, :]) + 2.0 ** -25
+        assert bool((err <= tol).all()), name + " epilogue"

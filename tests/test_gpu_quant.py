@@ -1,0 +1,125 @@
+"""GPU parity: group-wise weight quantization and the fused LayerNorm / GeLU
+front-ends against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import zq_inputs
+from helpers import assert_bit_equal, check_fused_codes, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def zq():
+    import paper_2206_01861_amd as lib
+    lib.lib()
+    return lib
+
+
+@pytest.fixture(scope="module")
+def orc():
+    from oracle import zq_oracle
+    return zq_oracle
+
+
+# ---------------------------------------------------------------- weights ----
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K,g", [
+    (768, 768, 48),        # BERT-base, 16 rows per group
+    (4096, 1024, 64),      # BERT-large FFC1
+    (1024, 4096, 64),      # BERT-large FFC2
+    (6144, 2048, 128),     # GPT-3 1.3B QKV, 48 rows per group
+    (16, 32, 1),           # smallest legal matrix
+    (96, 4128, 2),         # K not a multiple of the vector stride
+    (2048, 160, 128),
+])
+def test_weight_quant_bit_exact(zq, orc, bits, N, K, g):
+    print("weight quant", bits, N, K, g, flush=True)
+    rng = zq_inputs.rng_for(1, N + K + bits)
+    w = zq_inputs.weights(rng, N, K)
+    if g > 2:
+        w[(N // g):(2 * N // g)] = 0          # an all-zero group: codes 0, scale 0
+    wq_o, s_o, _ = orc.quantize_weight_groupwise(w, g, bits)
+    wq, s_w = zq.zq_quantize_weight_groupwise(dev(w), g, bits)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(s_w), s_o, "s_w")
+    assert_bit_equal(host(wq), wq_o, "wq")
+
+
+def test_weight_quant_fp16_extremes(zq, orc):
+    # subnormal-only group, a group holding the largest fp16, and exact ties
+    N, K, g = 48, 64, 3
+    w = np.zeros((N, K), np.float16)
+    w[0:16] = np.float16(6e-8) * np.arange(K, dtype=np.float16)[None, :]
+    w[16:32] = np.linspace(-65504, 65504, 16 * K).astype(np.float16).reshape(16, K)
+    w[32:48] = (np.arange(16 * K) % 255 - 127).astype(np.float16).reshape(16, K) * np.float16(0.5)
+    for bits in (8, 4):
+        wq_o, s_o, _ = orc.quantize_weight_groupwise(w, g, bits)
+        wq, s_w = zq.zq_quantize_weight_groupwise(dev(w), g, bits)
+        assert_bit_equal(host(s_w), s_o, "s_w")
+        assert_bit_equal(host(wq), wq_o, "wq")
+
+
+# ------------------------------------------------------------ front-ends ----
+ROW_SHAPES = [(1, 768), (7, 768), (33, 1024), (129, 2048), (5, 4096), (4, 6144), (3, 8192),
+              (2, 16384), (2, 24576), (9, 16), (6, 1040), (2, 32768)]
+
+
+@pytest.mark.parametrize("M,K", ROW_SHAPES)
+def test_layernorm_quant(zq, orc, M, K):
+    print("layernorm", M, K, flush=True)
+    rng = zq_inputs.rng_for(2, M + K)
+    x = zq_inputs.activations(rng, M, K, outlier_frac=0.01, outlier_scale=15.0, token_spread=True)
+    gamma, beta = zq_inputs.layernorm_params(rng, K)
+    xq, s_tok, y = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), dev(beta), 1e-5, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    xq, s_tok, y = host(xq), host(s_tok), host(y)
+    # the quantizer itself, on exactly the fp32 values the kernel quantized: bit-exact
+    xq_o, s_o = orc.quant_tokenwise(y)
+    assert_bit_equal(s_tok, s_o, "s_tok")
+    assert_bit_equal(xq, xq_o, "xq")
+    # the fused chain against the all-fp64 LayerNorm
+    y64, _ = orc.layernorm(x, gamma, beta, 1e-5)
+    n_mis = check_fused_codes(xq, s_tok, y, y64, "layernorm %dx%d" % (M, K))
+    assert n_mis <= max(4, int(1e-3 * M * K))
+
+
+def test_layernorm_options(zq, orc):
+    rng = zq_inputs.rng_for(2, 999)
+    M, K = 12, 1024
+    x = zq_inputs.activations(rng, M, K, n_outliers=4, outlier_scale=20.0)
+    x[5] = np.float16(1.25)          # constant row: zero variance, y = beta
+    gamma, beta = zq_inputs.layernorm_params(rng, K)
+    # no beta, fp16 tap, other eps
+    xq, s_tok, y16 = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), None, 1e-12, y_dtype=torch.float16)
+    y64, _ = orc.layernorm(x, gamma, None, 1e-12)
+    check_fused_codes(host(xq), host(s_tok), None, y64, "layernorm no beta")
+    assert np.abs(host(y16).astype(np.float64) - y64).max() <= 1e-3 * np.abs(y64).max()
+    assert host(s_tok)[5] == 0 and not host(xq)[5].any()      # zero row: codes 0, scale 0
+    # no tap at all gives the same codes as with the tap
+    xq2, s2, none = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), None, 1e-12)
+    assert none is None
+    assert torch.equal(xq2, xq) and torch.equal(s2, s_tok)
+
+
+@pytest.mark.parametrize("approx", [False, True])
+@pytest.mark.parametrize("M,N", [(1, 4096), (7, 3072), (33, 8192), (3, 16384), (2, 24576), (130, 768)])
+def test_gelu_quant(zq, orc, approx, M, N):
+    print("gelu", approx, M, N, flush=True)
+    rng = zq_inputs.rng_for(3, M + N)
+    h = (zq_inputs.activations(rng, M, N, outlier_frac=0.01, outlier_scale=6.0).astype(np.float32) * 1.5).astype(np.float16)
+    bias = zq_inputs.bias(rng, N, std=0.2)
+    xq, s_tok, y = zq.zq_gelu_quant_tokenwise(dev(h), dev(bias), approx_tanh=approx, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    xq, s_tok, y = host(xq), host(s_tok), host(y)
+    xq_o, s_o = orc.quant_tokenwise(y)
+    assert_bit_equal(s_tok, s_o, "s_tok")
+    assert_bit_equal(xq, xq_o, "xq")
+    y64, _ = orc.gelu(h, bias, approx_tanh=approx)
+    n_mis = check_fused_codes(xq, s_tok, y, y64, "gelu %dx%d" % (M, N))
+    assert n_mis <= max(4, int(1e-3 * M * N))
+    # bias is optional
+    xq_nb, s_nb, y_nb = zq.zq_gelu_quant_tokenwise(dev(h), None, approx_tanh=approx, y_dtype=torch.float32)
+    y64_nb, _ = orc.gelu(h, None, approx_tanh=approx)
+    check_fused_codes(host(xq_nb), host(s_nb), host(y_nb), y64_nb, "gelu no bias")
