@@ -152,6 +152,7 @@ const char *zq_gemm_variant_name(int variant) {
         case zq::kGemmTile256: return "tile256";
         case zq::kGemmSkinny: return "skinny";
         case zq::kGemmSkinnySplitK: return "skinny_splitk";
+        case zq::kGemmTile256x128: return "tile256x128";
     }
     return nullptr;
 }

@@ -59,4 +59,12 @@ __device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
            ((uint32_t)(d & 0xff) << 24);
 }
 
+// Workgroup barrier for kernels that keep asynchronous global->LDS loads in flight across it.
+// __syncthreads() carries a fence that drains every outstanding vector-memory operation
+// (s_waitcnt vmcnt(0)), which would serialise the load pipeline; here only LDS traffic is
+// drained, and the "memory" clobber keeps the compiler from moving accesses across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 }  // namespace zq

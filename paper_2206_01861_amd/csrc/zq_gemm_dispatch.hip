@@ -24,11 +24,12 @@ bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t 
             return true;
         case kGemmTile128:
         case kGemmTile256:
+        case kGemmTile256x128:
             return (K % 128) == 0;
         case kGemmSkinny:
-            return M <= 64 && (K % (w_bits == 8 ? 128 : 256)) == 0;
+            return M <= 64 && (K % 256) == 0;
         case kGemmSkinnySplitK:
-            return M <= 64 && (K % (w_bits == 8 ? 128 : 256)) == 0 &&
+            return M <= 64 && (K % 256) == 0 &&
                    workspace_bytes >= gemm_variant_workspace(variant, M, N, K, w_bits);
     }
     return false;
@@ -39,6 +40,7 @@ hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st) {
         case kGemmSimple: return launch_gemm_simple(a, st);
         case kGemmTile128: return launch_gemm_tile(a, 128, st);
         case kGemmTile256: return launch_gemm_tile(a, 256, st);
+        case kGemmTile256x128: return launch_gemm_tile(a, 192, st);
         case kGemmSkinny: return launch_gemm_skinny(a, false, st);
         case kGemmSkinnySplitK: return launch_gemm_skinny(a, true, st);
     }

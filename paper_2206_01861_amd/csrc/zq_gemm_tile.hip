@@ -2,18 +2,24 @@
 // (Sec. 4.3 "INT8 GeMM"; App. D "Dequantization Associated with GeMM
 // Schedule").  Bound by the INT8 matrix cores.
 //
-// A 256-thread workgroup (2 x 2 waves) owns a BM x BN output tile.  Per
-// 128-byte step of K both operand tiles go from global memory straight into
-// LDS with 16-byte direct loads (no register staging), double buffered; rows
-// are 128 bytes with their 16-byte chunks XOR-swizzled so that the
+// A workgroup of WAVES_M x WAVES_N waves owns a BM x BN output tile.  Per BK
+// bytes of K both operand tiles go from global memory straight into LDS with
+// 16-byte direct loads (no register staging) through a ring of NSTAGE stages;
+// rows are BK bytes with their 16-byte chunks XOR-swizzled so that the
 // ds_read_b128 of a matrix-core fragment (32 rows, one chunk) is free of bank
-// conflicts.  Each wave computes (BN/2) x (BM/2) with v_mfma_i32_32x32x32_i8,
-// the weight fragment as the first operand, so every group of four accumulator
-// registers runs along the output columns.  The epilogue scales the INT32
-// accumulators by s_tok[row] * s_w[group], adds the bias, rounds to FP16,
-// transposes the wave's tile through LDS (free after the main loop) and writes
-// rows of 256 contiguous bytes.  INT4 weights are unpacked to INT8 (times 16)
-// on their way into LDS and the factor is shifted out of the accumulator.
+// conflicts.  Each wave computes (BN/WAVES_N) x (BM/WAVES_M) with
+// v_mfma_i32_32x32x32_i8, the weight fragment as the first operand, so every
+// group of four accumulator registers runs along the output columns.  Two
+// fragment sets alternate so the LDS reads of k step s+1 are in flight under
+// the MFMAs of step s; with two waves per SIMD the barrier and epilogue of one
+// wave overlap the matrix-core work of the other.
+//
+// The epilogue scales the INT32 accumulators by s_tok[row] * s_w[group], adds
+// the bias and rounds to FP16 (scales and bias were staged in LDS before the
+// main loop), passes 32 rows at a time through a wave-private LDS buffer and
+// writes full contiguous row segments.  INT4 weights are unpacked to INT8
+// (times 16) on their way into LDS and the factor is shifted out of the
+// accumulator.
 //
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
@@ -28,7 +34,11 @@ namespace {
 constexpr uint32_t kRsrcFlags = 0x00020000u;
 typedef __attribute__((address_space(3))) void lds_void;
 
-__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// Chunk swizzle: 16 consecutive rows reading the same logical chunk hit 16 different bank groups.
+template <int BK>
+__device__ __forceinline__ int swz(int row) {
+    return (BK == 128) ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3);
+}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -43,27 +53,47 @@ __device__ __forceinline__ void unpack8_nat(uint32_t p, uint32_t &d0, uint32_t &
     d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);   // lo2 hi2 lo3 hi3
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE>
+struct TileCfg {
+    static constexpr int kWaves = WAVES_M * WAVES_N;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kStage = (BM + BN) * BK;
+    static constexpr int kWN = BN / WAVES_N;
+    static constexpr int kEpiRow = kWN * 2 + 16;              // padded FP16 row of the wave-private buffer
+    static constexpr int kEpi = kWaves * 32 * kEpiRow;
+    static constexpr int kMain = NSTAGE * kStage > kEpi ? NSTAGE * kStage : kEpi;
+    static constexpr int kLds = kMain + (2 * BN + BM) * 4;    // + column scale, column bias, row scale
+};
+
 }  // namespace
 
-template <int BM, int BN, int WBITS>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict__ xq, const float *__restrict__ s_tok,
-                                                        const uint8_t *__restrict__ wq, const float *__restrict__ s_w,
-                                                        int gs, const half_t *__restrict__ bias, int M, int N, int K,
-                                                        half_t *__restrict__ out, int32_t *__restrict__ acc_out,
-                                                        int tiles_m, int tiles_n) {
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
+    const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
+    const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    constexpr int BK = 128;
+    constexpr int NW = Cfg::kWaves;
+    constexpr int NT = Cfg::kThreads;
     constexpr int X_STAGE = BM * BK;
-    constexpr int W_STAGE = BN * BK;
-    constexpr int STAGE = X_STAGE + W_STAGE;
-    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int STAGE = Cfg::kStage;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
-    constexpr int XU = BM / 8;                       // 1 KB load units (8 rows) in the activation tile
-    constexpr int WU = BN / 8;
+    constexpr int KSTEPS = BK / 32;
+    constexpr int CPR = BK / 16;                     // 16-byte chunks per row
+    constexpr int RPU = 64 / CPR;                    // rows per 1 KB load unit
+    constexpr int XU = BM / RPU;                     // load units in the activation tile
+    constexpr int WU = BN / RPU;
     constexpr int DIRECT_UNITS = (WBITS == 8) ? (XU + WU) : XU;
-    constexpr int LPS = DIRECT_UNITS / 4;            // direct loads per wave per stage
-    constexpr int W4_PASSES = BN / 64;               // INT4: 4 threads per row, 64 rows per pass
+    static_assert(XU % NW == 0 && WU % NW == 0, "load units must split evenly over the waves");
+    constexpr int LPS = DIRECT_UNITS / NW;           // direct loads per wave per stage
+    constexpr int TPR4 = BK / 32;                    // INT4: threads per row (16 packed bytes each)
+    constexpr int W4_ROWS = NT / TPR4;               // rows per pass
+    constexpr int W4_PASSES = (BN + W4_ROWS - 1) / W4_ROWS;
+    static_assert(BN % W4_ROWS == 0 || BN < W4_ROWS, "INT4 passes must tile the weight rows");
 
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -90,32 +120,33 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(xq), 0, (int)((size_t)M * K), kRsrcFlags);
 
     // ---- per-lane source offsets of this wave's direct-load units ---------
-    // unit u < XU: activation rows u*8..u*8+7; else weight rows.  Rows past the
-    // matrix edge are clamped to the last row: loaded, multiplied, never stored.
+    // Wave w takes units w, w+NW, ...; units below XU are activation rows, the
+    // rest weight rows.  Rows past the matrix edge are clamped to the last row:
+    // loaded, multiplied, never stored.
     int voff[LPS];
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
-        const int u = wave + 4 * i;
-        if (u < XU) {
-            const int row = u * 8 + lane / 8;
+        const int u = wave + NW * i;
+        if (i < XU / NW) {
+            const int row = u * RPU + lane / CPR;
             int grow = m0 + row;
             if (grow > M - 1) grow = M - 1;
-            voff[i] = grow * K + (((lane % 8) ^ swz(row)) * 16);
+            voff[i] = grow * K + (((lane % CPR) ^ swz<BK>(row)) * 16);
         } else {
-            const int row = (u - XU) * 8 + lane / 8;
+            const int row = (u - XU) * RPU + lane / CPR;
             int grow = n0 + row;
             if (grow > N - 1) grow = N - 1;
-            voff[i] = grow * wrow_bytes + (((lane % 8) ^ swz(row)) * 16);
+            voff[i] = grow * wrow_bytes + (((lane % CPR) ^ swz<BK>(row)) * 16);
         }
     }
-    // INT4 weights: thread -> (row = pass*64 + tid/4, 16 packed bytes = 32 codes = chunks 2q, 2q+1)
-    int w4_voff[W4_PASSES > 0 ? W4_PASSES : 1];
+    // INT4 weights: thread -> (row = pass*W4_ROWS + tid/TPR4, 16 packed bytes = 32 codes = chunks 2q, 2q+1)
+    int w4_voff[W4_PASSES];
     if (WBITS == 4) {
 #pragma unroll
         for (int p = 0; p < W4_PASSES; ++p) {
-            int grow = n0 + p * 64 + (int)threadIdx.x / 4;
+            int grow = n0 + p * W4_ROWS + (int)threadIdx.x / TPR4;
             if (grow > N - 1) grow = N - 1;
-            w4_voff[p] = grow * wrow_bytes + ((int)threadIdx.x % 4) * 16;
+            w4_voff[p] = grow * wrow_bytes + ((int)threadIdx.x % TPR4) * 16;
         }
     }
 
@@ -123,8 +154,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict
         uint8_t *base = smem + slot * STAGE;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
-            const int u = wave + 4 * i;
-            if (u < XU)
+            const int u = wave + NW * i;
+            if (i < XU / NW)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[i], kt * BK, 0,
                                                          0);
             else
@@ -132,7 +163,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict
                                                          voff[i], kt * BK, 0, 0);
         }
     };
-    int32x4 w4_regs[W4_PASSES > 0 ? W4_PASSES : 1];
+    int32x4 w4_regs[W4_PASSES];
     auto w4_fetch = [&](int kt) {
 #pragma unroll
         for (int p = 0; p < W4_PASSES; ++p)
@@ -142,18 +173,20 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict
         uint8_t *base = smem + slot * STAGE + X_STAGE;
 #pragma unroll
         for (int p = 0; p < W4_PASSES; ++p) {
-            const int row = p * 64 + (int)threadIdx.x / 4;
-            const int q = (int)threadIdx.x % 4;
-            uint32_t d[8];
-            unpack8_nat((uint32_t)w4_regs[p][0], d[0], d[1]);
-            unpack8_nat((uint32_t)w4_regs[p][1], d[2], d[3]);
-            unpack8_nat((uint32_t)w4_regs[p][2], d[4], d[5]);
-            unpack8_nat((uint32_t)w4_regs[p][3], d[6], d[7]);
-            const int s = swz(row);
-            *reinterpret_cast<int32x4 *>(base + row * BK + (((2 * q) ^ s) * 16)) =
-                int32x4{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
-            *reinterpret_cast<int32x4 *>(base + row * BK + (((2 * q + 1) ^ s) * 16)) =
-                int32x4{(int)d[4], (int)d[5], (int)d[6], (int)d[7]};
+            const int row = p * W4_ROWS + (int)threadIdx.x / TPR4;
+            const int q = (int)threadIdx.x % TPR4;
+            if (BN >= W4_ROWS || row < BN) {
+                uint32_t d[8];
+                unpack8_nat((uint32_t)w4_regs[p][0], d[0], d[1]);
+                unpack8_nat((uint32_t)w4_regs[p][1], d[2], d[3]);
+                unpack8_nat((uint32_t)w4_regs[p][2], d[4], d[5]);
+                unpack8_nat((uint32_t)w4_regs[p][3], d[6], d[7]);
+                const int s = swz<BK>(row);
+                *reinterpret_cast<int32x4 *>(base + row * BK + (((2 * q) ^ s) * 16)) =
+                    int32x4{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+                *reinterpret_cast<int32x4 *>(base + row * BK + (((2 * q + 1) ^ s) * 16)) =
+                    int32x4{(int)d[4], (int)d[5], (int)d[6], (int)d[7]};
+            }
         }
     };
 
@@ -166,137 +199,203 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const int8_t *__restrict
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[fn][fm][e] = 0;
 
-    const int wm = wave % 2, wn = wave / 2;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int lr = lane % 32;                // fragment row supplied by this lane
     const int lc = lane / 32;                // which 16-byte half of the 32-byte k step
-    const int sw = swz(lr);                  // wave and fragment offsets are multiples of 32 rows
+    const int sw = swz<BK>(lr);              // wave and fragment offsets are multiples of 32 rows
     const int x_off = (wm * WM + lr) * BK;
     const int w_off = X_STAGE + (wn * WN + lr) * BK;
 
-    const int nkt = K / BK;
-    issue_direct(0, 0);
-    if (WBITS == 4) {
-        w4_fetch(0);
-        w4_store(0);
+    // Fragment loads and matrix-core steps of one 32-byte k step, in the order
+    // the MFMAs consume them: a[0], every bx, then the remaining a.
+    auto read_frags = [&](const uint8_t *sb, int ks, int32x4(&a)[FN], int32x4(&bx)[FM]) {
+        const int p = ((ks * 2 + lc) ^ sw) * 16;
+        a[0] = *reinterpret_cast<const int32x4 *>(sb + w_off + p);
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
+#pragma unroll
+        for (int fn = 1; fn < FN; ++fn) a[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BK + p);
+    };
+    auto mfma_step = [&](const int32x4(&a)[FN], const int32x4(&bx)[FM]) {
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm)
+                acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
+    };
+    // one LDS read after every (FN*FM)/(FN+FM) MFMAs
+    auto interleave = [&]() {
+        constexpr int per_read = (FN * FM) / (FN + FM) > 0 ? (FN * FM) / (FN + FM) : 1;
+#pragma unroll
+        for (int i = 0; i < FN + FM; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, per_read, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // DS read
+        }
+    };
+
+    // Scale prefetch (App. D reads both scale vectors before the product is complete): the
+    // per-column weight-group scale and bias and the per-row token scale of this tile go to LDS now.
+    float *col_scale = reinterpret_cast<float *>(smem + Cfg::kMain);
+    float *col_bias = col_scale + BN;
+    float *row_scale = col_bias + BN;
+    for (int c = threadIdx.x; c < BN; c += NT) {
+        int n = n0 + c;
+        if (n > N - 1) n = N - 1;
+        col_scale[c] = s_w[n / gs];
+        col_bias[c] = (bias != nullptr) ? (float)bias[n] : 0.0f;
     }
+    for (int r = threadIdx.x; r < BM; r += NT) {
+        int m = m0 + r;
+        if (m > M - 1) m = M - 1;
+        row_scale[r] = s_tok[m];
+    }
+
+    // ---- main loop ----------------------------------------------------------
+    // Stage kt lives in slot kt % NSTAGE.  During the last k step of stage kt every wave already holds
+    // that step's fragments in registers, so after the barrier there the slot is free and receives
+    // stage kt + NSTAGE, while the first fragments of stage kt + 1 are read under the last MFMAs.
+    const int nkt = K / BK;
+    int32x4 a0[FN], b0[FM], a1[FN], b1[FM];
+#pragma unroll
+    for (int s = 0; s < NSTAGE; ++s) {
+        if (s < nkt) {
+            issue_direct(s, s);
+            if (WBITS == 4) {
+                w4_fetch(s);
+                w4_store(s);
+            }
+        }
+    }
+    if (WBITS == 8 && nkt >= NSTAGE)
+        wait_vmcnt<(NSTAGE - 1) * LPS>();      // stage 0 has landed; later stages may still be in flight
+    else
+        wait_vmcnt<0>();
+    __syncthreads();
+    read_frags(smem, 0, a0, b0);
+
     for (int kt = 0; kt < nkt; ++kt) {
-        wait_vmcnt<0>();                     // this wave's loads of stage kt have landed
-        __syncthreads();                     // ... and everyone's; stage kt-1 is no longer being read
-        const int nxt = (kt + 1) & 1;
-        if (kt + 1 < nkt) {
-            issue_direct(kt + 1, nxt);
-            if (WBITS == 4) w4_fetch(kt + 1);
+        const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
+        const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            int32x4(&ca)[FN] = (ks & 1) ? a1 : a0;
+            int32x4(&cb)[FM] = (ks & 1) ? b1 : b0;
+            int32x4(&na)[FN] = (ks & 1) ? a0 : a1;
+            int32x4(&nb2)[FM] = (ks & 1) ? b0 : b1;
+            if (ks + 1 < KSTEPS) {
+                read_frags(sb, ks + 1, na, nb2);
+                mfma_step(ca, cb);
+                interleave();
+                if (WBITS == 4 && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < nkt)
+                    w4_store((kt + NSTAGE - 1) % NSTAGE);     // registers fetched at the previous stage boundary
+            } else {
+                if (kt + 1 < nkt) {
+                    if (WBITS == 8 && kt + NSTAGE - 1 < nkt)
+                        wait_vmcnt<(NSTAGE - 2) * LPS>();     // stage kt+1 has landed
+                    else
+                        wait_vmcnt<0>();
+                    lds_barrier();
+                    if (kt + NSTAGE < nkt) {
+                        issue_direct(kt + NSTAGE, kt % NSTAGE);
+                        if (WBITS == 4) w4_fetch(kt + NSTAGE);
+                    }
+                    read_frags(sn, 0, na, nb2);
+                }
+                mfma_step(ca, cb);
+            }
         }
-        const uint8_t *sb = smem + (kt & 1) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            const int p = ((ks * 2 + lc) ^ sw) * 16;
-            int32x4 a[FN], bx[FM];
-#pragma unroll
-            for (int fn = 0; fn < FN; ++fn) a[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BK + p);
-#pragma unroll
-            for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
-#pragma unroll
-            for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-                for (int fm = 0; fm < FM; ++fm)
-                    acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
-        }
-        if (WBITS == 4 && kt + 1 < nkt) w4_store(nxt);   // slot nxt was last read before this iteration's barrier
     }
 
     // ---- epilogue ---------------------------------------------------------
     // acc[fn][fm][v]: output column n = wn*WN + fn*32 + 8*(v/4) + 4*(lane/32) + v%4,
     //                 token row     m = wm*WM + fm*32 + lane%32.
     __syncthreads();                          // all reads of the last stage are done; LDS is reused below
-    constexpr int OROW = WN * 2 + 16;         // padded row of the wave's FP16 tile in LDS
-    // (the launcher sizes dynamic LDS as max(2 * STAGE, 4 * WM * OROW))
-    uint8_t *ot = smem + wave * (WM * OROW);
+    constexpr int OROW = Cfg::kEpiRow;
+    uint8_t *ot = smem + wave * (32 * OROW);  // wave-private: 32 rows of this wave's columns
     const int mw = m0 + wm * WM;              // first token row of this wave
     const int nw = n0 + wn * WN;              // first output column of this wave
+    constexpr int LPR = WN * 2 / 16;          // lanes per output row (16 bytes each)
+    constexpr int RPI = 64 / LPR;             // rows per store instruction
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
-        const int m = mw + fm * 32 + lr;
-        const float st = s_tok[m < M ? m : M - 1];
+        const float st = row_scale[wm * WM + fm * 32 + lr];
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int nl = fn * 32 + 8 * q + 4 * lc;
-                int n = nw + nl;
-                if (n > N - 4) n = N - 4;     // columns past N are never stored; keep the loads in range
-                const float sc = st * s_w[n / gs];
+                const float4 sc = *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
+                const float4 cb = *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
                 int32x4 v = {acc[fn][fm][4 * q], acc[fn][fm][4 * q + 1], acc[fn][fm][4 * q + 2],
                              acc[fn][fm][4 * q + 3]};
                 if (WBITS == 4) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] >>= 4;
+                    for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
                 }
                 half4 o;
-                if (bias != nullptr) {
-                    const half4 bv = *reinterpret_cast<const half4 *>(bias + n);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (half_t)((float)v[e] * sc + (float)bv[e]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (half_t)((float)v[e] * sc);
+                o[0] = (half_t)((float)v[0] * (st * sc.x) + cb.x);
+                o[1] = (half_t)((float)v[1] * (st * sc.y) + cb.y);
+                o[2] = (half_t)((float)v[2] * (st * sc.z) + cb.z);
+                o[3] = (half_t)((float)v[3] * (st * sc.w) + cb.w);
+                *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
+                if (acc_out != nullptr) {
+                    const int m = mw + fm * 32 + lr;
+                    if (m < M && nw + nl < N) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
                 }
-                *reinterpret_cast<half4 *>(ot + (fm * 32 + lr) * OROW + nl * 2) = o;
-                if (acc_out != nullptr && m < M && nw + nl < N)
-                    *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
             }
         }
-    }
-    // Each wave reads back its own tile only: a wave-local exchange, no workgroup barrier needed,
-    // but the LDS writes above must have completed.
-    __builtin_amdgcn_s_waitcnt(0xc07f);       // lgkmcnt(0)
-    constexpr int LPR = WN * 2 / 16;          // lanes per output row (16 bytes each)
-    constexpr int RPI = 64 / LPR;             // rows per store instruction
+        // The wave reads back its own 32 rows (LDS operations of one wave complete in order) and
+        // stores whole row segments.
 #pragma unroll
-    for (int i = 0; i < WM / RPI; ++i) {
-        const int row = i * RPI + lane / LPR;
-        const int col = (lane % LPR) * 8;
-        const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
-        const int m = mw + row;
-        const int n = nw + col;
-        if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + lane / LPR;
+            const int col = (lane % LPR) * 8;
+            const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
+            const int m = mw + fm * 32 + row;
+            const int n = nw + col;
+            if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+        }
     }
 #endif
 }
 
 namespace {
 
-template <int BM, int BN, int WBITS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS>
 hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st) {
-    constexpr int STAGE = (BM + BN) * 128;
-    constexpr int OROW = BN + 16;
-    constexpr size_t lds_main = 2 * STAGE;
-    constexpr size_t lds_epi = 4 * (BM / 2) * OROW;
-    constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
+    constexpr size_t lds = Cfg::kLds;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WBITS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WBITS>), dim3(tiles_m * tiles_n), dim3(256), lds, st, a.xq, a.s_tok,
-                       reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
-                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
-                       a.acc_out, tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS>), dim3(tiles_m * tiles_n),
+                       dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq), a.s_w,
+                       a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
+                       reinterpret_cast<half_t *>(a.out), a.acc_out, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// block: 256 = 256x256 tile, eight waves; 192 = 256x128 tile, four waves, two workgroups per CU;
+//        128 = 128x128 tile, four waves.
 hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     if (block == 256) {
-        if (a.w_bits == 8) return launch_tile_t<256, 256, 8>(a, st);
-        return launch_tile_t<256, 256, 4>(a, st);
+        if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8>(a, st);
+        return launch_tile_t<256, 256, 2, 4, 128, 2, 4>(a, st);
     }
-    if (a.w_bits == 8) return launch_tile_t<128, 128, 8>(a, st);
-    return launch_tile_t<128, 128, 4>(a, st);
+    if (block == 192) {
+        if (a.w_bits == 8) return launch_tile_t<256, 128, 2, 2, 64, 3, 8>(a, st);
+        return launch_tile_t<256, 128, 2, 2, 64, 3, 4>(a, st);
+    }
+    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 64, 4, 8>(a, st);
+    return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
 }
 
 }  // namespace zq

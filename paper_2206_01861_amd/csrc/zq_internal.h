@@ -19,11 +19,12 @@ hipError_t launch_weight_quant(const void *w, int N, int K, int groups, int bits
 // GeMM schedules.  The order is part of the test/tuning hook of the C ABI.
 enum GemmVariant {
     kGemmSimple = 0,      // one wave per 16x16 tile, operands from global; any legal shape
-    kGemmTile128 = 1,     // 128x128 block tile, LDS staged
-    kGemmTile256 = 2,     // 256x256 block tile, LDS staged
-    kGemmSkinny = 3,      // M <= 64: weight streaming, reduction split inside the workgroup
-    kGemmSkinnySplitK = 4,// M <= 64: reduction also split across workgroups (needs workspace)
-    kGemmVariantCount = 5
+    kGemmTile128 = 1,     // 128x128 block tile, four waves
+    kGemmTile256 = 2,     // 256x256 block tile, eight waves
+    kGemmSkinny = 3,      // M <= 64: weight streaming, whole K in one workgroup
+    kGemmSkinnySplitK = 4,// M <= 64: K also split across workgroups (needs workspace)
+    kGemmTile256x128 = 5, // 256x128 block tile, four waves, two workgroups per CU
+    kGemmVariantCount = 6
 };
 
 struct GemmArgs {

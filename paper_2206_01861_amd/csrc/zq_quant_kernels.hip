@@ -42,13 +42,30 @@ __device__ __forceinline__ float row_max(float v, float *lds) {
     return v;
 }
 
+// GeLU, erf form: u * Phi(u) with Phi from the rational erfc approximation of
+// Abramowitz & Stegun 7.1.26 (absolute error of erf below 1.5e-7, i.e. below
+// fp32 resolution of Phi), evaluated as 0.5 * erfc(|u|/sqrt2) so that the tail
+// keeps its relative accuracy.  About a third of the VALU work of the library
+// erff, which otherwise makes this memory-bound kernel compute-bound.
 __device__ __forceinline__ float gelu_erf(float u) {
-    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+    const float z = fabsf(u) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);
+    const float half_erfc = 0.5f * (p * t) * e;
+    const float phi = (u >= 0.0f) ? 1.0f - half_erfc : half_erfc;
+    return u * phi;
 }
 
+// GeLU, tanh form: 0.5 u (1 + tanh(v)) = u * (1 - 1 / (1 + exp(2v))).
 __device__ __forceinline__ float gelu_tanh(float u) {
     const float c = 0.79788456080286535588f;
-    return 0.5f * u * (1.0f + tanhf(c * (u + 0.044715f * u * u * u)));
+    const float v = c * fmaf(0.044715f * u * u, u, u);
+    const float e = __builtin_amdgcn_exp2f(v * (2.0f * 1.44269504088896340736f));
+    return u * (1.0f - __builtin_amdgcn_rcpf(1.0f + e));
 }
 
 template <int OP, int TPR, int VPT>

@@ -40,7 +40,7 @@ def test_status_strings_and_version():
 
 
 def test_variant_table():
-    names = [zq.gemm_variant_name(i) for i in range(8)]
+    names = [zq.gemm_variant_name(i) for i in range(9)]
     assert names[0] == "simple" and None in names
     # decode shapes go to a weight-streaming schedule, prefill shapes to a tiled one
     assert zq.gemm_variant_name(zq.gemm_choose_variant(1, 6144, 2048)).startswith("skinny")

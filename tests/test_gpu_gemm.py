@@ -10,7 +10,7 @@ from helpers import assert_bit_equal, assert_out_close, dev, freivalds_gpu, host
 
 pytestmark = pytest.mark.gpu
 
-SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK = range(5)
+SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK, TILE256X128 = range(6)
 
 
 @pytest.fixture(scope="module")
@@ -68,9 +68,11 @@ SHAPES = [
     (TILE128, 1, 16, 128, 1), (TILE128, 515, 1024, 1024, 64),
     (TILE256, 256, 256, 128, 16), (TILE256, 300, 528, 512, 33), (TILE256, 1030, 768, 256, 48),
     (TILE256, 17, 16, 384, 1),
-    (SKINNY, 1, 64, 128, 4), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
+    (TILE256X128, 256, 128, 128, 8), (TILE256X128, 300, 400, 512, 25), (TILE256X128, 1030, 272, 256, 17),
+    (TILE256X128, 17, 16, 384, 1), (TILE256X128, 512, 1024, 1024, 64),
+    (SKINNY, 1, 64, 256, 4), (SKINNY, 3, 128, 768, 8), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
     (SKINNY, 16, 208, 1280, 13), (SKINNY, 17, 80, 512, 5), (SKINNY, 32, 2048, 2048, 128),
-    (SKINNY, 33, 144, 896, 9), (SKINNY, 64, 1024, 1536, 64), (SKINNY, 50, 16, 256, 1),
+    (SKINNY, 33, 144, 1792, 9), (SKINNY, 64, 1024, 1536, 64), (SKINNY, 50, 16, 256, 1),
     (SKINNY_SPLITK, 1, 2048, 8192, 128), (SKINNY_SPLITK, 8, 256, 4096, 16), (SKINNY_SPLITK, 32, 2048, 8192, 128),
     (SKINNY_SPLITK, 64, 1024, 6144, 64), (SKINNY_SPLITK, 13, 80, 2304, 5),
 ]
@@ -82,8 +84,8 @@ def test_gemm_against_oracle(zq, orc, bits, variant, M, N, K, g):
     print("gemm", zq.gemm_variant_name(variant), bits, M, N, K, g, flush=True)
     if bits == 4 and K % 32:
         pytest.skip("INT4 needs K % 32 == 0")
-    if bits == 4 and variant in (SKINNY, SKINNY_SPLITK) and K % 256:
-        pytest.skip("INT4 streaming schedule steps K by 256")
+    if variant in (SKINNY, SKINNY_SPLITK) and K % 256:
+        pytest.skip("the streaming schedule steps K by 256")
     rng = zq_inputs.rng_for(4, variant * 1000 + M + N + K + bits)
     xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
     ws = None
@@ -104,7 +106,7 @@ def test_no_bias_and_extreme_codes(zq, orc):
     wq[1::2] = -127
     s_tok = np.full(M, 1e-3, np.float32)
     s_w = np.full(g, 1e-4, np.float32)
-    for variant in (SIMPLE, TILE128, SKINNY):
+    for variant in (SIMPLE, TILE128, TILE256, TILE256X128, SKINNY):
         res = _run(zq, 8, variant, xq, s_tok, wq, s_w, None)
         acc = host(res[1])
         assert (acc[:, 0::2] == 16129 * K).all() and (acc[:, 1::2] == -16129 * K).all()
