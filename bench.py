@@ -4,16 +4,18 @@
 Default run (`python bench.py`): the BERT-large feed-forward pair of the
 paper's BERT-large workload (batch 32 x sequence 128 = 4096 tokens),
   LayerNorm+quant -> INT8 GeMM 1024->4096 (+bias) -> GeLU+quant -> INT8 GeMM 4096->1024 (+bias),
-with inputs resident in HBM.  A step is one pass of that chain.  Prints ONE JSON
-line: whole-chain throughput in TOPS, the roofline of the dominant kernel (the
-tiled INT8 GeMM, launched twice per step), the same chain in FP16 through
-torch (hipBLASLt / rocBLAS) as the speed-up comparator, and the CPU oracle
+with inputs resident in HBM.  A step is one pass of that chain.  The chain is
+captured once into a HIP graph and replayed (the paper replays a CUDA graph for
+both its INT8 and its FP16 runs, App. D); the FP16 comparator is captured the
+same way.  Prints ONE JSON line: whole-chain throughput in TOPS, the roofline
+of the dominant kernel (the tiled INT8 GeMM, launched twice per step), the
+same chain in FP16 through torch (hipBLASLt / rocBLAS), and the CPU oracle
 timed on the host cores.
 
-`python bench.py --table` additionally times every linear of every workload
-shape (prefill: TOPS vs the INT8 matrix-core peak; decode: GB/s vs HBM, with
-buffers rotated through more than 512 MB so the Infinity Cache cannot serve
-them) and writes gpurun_out/bench_table.json; it prints nothing else.
+`python bench.py --table` instead times every linear of every workload shape
+(prefill: TOPS against the INT8 matrix-core peak; decode: GB/s against HBM,
+with buffers rotated through more than 512 MB so the Infinity Cache cannot
+serve them) and writes gpurun_out/bench_table.json; the table goes to stderr.
 """
 import argparse
 import json
@@ -30,8 +32,11 @@ sys.path.insert(0, ROOT)
 import zq_inputs  # noqa: E402
 
 PEAK_INT8_TOPS = 5000.0    # MI355X dense INT8 matrix-core peak, TOP/s
-PEAK_FP16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes one tiled-GeMM launch of the default workload moves, mean of the two launches of a
+# step: rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy
+# (profiles/c2_ffc_pair_hbm_traffic.txt; algorithmic bytes are 40 MiB and 28 MiB).
+GEMM_TRAFFIC_BYTES = 56.2 * (1 << 20)
 
 
 def _events(n):
@@ -42,8 +47,37 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def graph_of(fn, reps):
+    """Capture `reps` calls of fn(i) on a side stream into one HIP graph."""
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for i in range(min(reps, 3)):
+            fn(i)                      # warm up outside the capture (lazy module load, attributes)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(reps):
+            fn(i)
+    return g
+
+
+def time_graph(g, replays, reps_per_replay, warm=2):
+    for _ in range(warm):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = _events(2)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * reps_per_replay)      # ms per call
+
+
 class FFCPair:
-    """Workload c2: tensors resident on the GPU, weights quantized once (offline step)."""
+    """Workload c2: tensors resident on the GPU, weights quantized once (the offline step)."""
 
     def __init__(self, zq, tokens=4096, hidden=1024, ffn=4096, groups=64):
         self.zq = zq
@@ -55,10 +89,9 @@ class FFCPair:
         self.w2_h, self.b2_h = zq_inputs.weights(rng, hidden, ffn), zq_inputs.bias(rng, hidden)
         self.x, self.gamma, self.beta = _dev(self.x_h), _dev(self.gamma_h), _dev(self.beta_h)
         self.w1, self.b1, self.w2, self.b2 = _dev(self.w1_h), _dev(self.b1_h), _dev(self.w2_h), _dev(self.b2_h)
-        t0 = torch.cuda.Event(enable_timing=True)
-        t1 = torch.cuda.Event(enable_timing=True)
         zq.zq_quantize_weight_groupwise(self.w1, groups, 8)      # warm
         torch.cuda.synchronize()
+        t0, t1 = _events(2)
         t0.record()
         self.wq1, self.sw1 = zq.zq_quantize_weight_groupwise(self.w1, groups, 8)
         self.wq2, self.sw2 = zq.zq_quantize_weight_groupwise(self.w2, groups, 8)
@@ -75,24 +108,25 @@ class FFCPair:
         self.ops = 2.0 * tokens * (hidden * ffn + ffn * hidden)
         self.gemm_ops = 2.0 * tokens * hidden * ffn          # per GeMM launch (both are equal)
 
-    def step(self, ev=None):
-        zq = self.zq
-        if ev is not None:
-            ev[0].record()
-        zq.zq_layernorm_quant_tokenwise(self.x, self.gamma, self.beta, 1e-5, out=(self.xq, self.st))
-        if ev is not None:
-            ev[1].record()
-        zq.zq_gemm_i8_dequant(self.xq, self.st, self.wq1, self.sw1, self.b1, out=self.h)
-        if ev is not None:
-            ev[2].record()
-        zq.zq_gelu_quant_tokenwise(self.h, None, out=(self.hq, self.st2))
-        if ev is not None:
-            ev[3].record()
-        zq.zq_gemm_i8_dequant(self.hq, self.st2, self.wq2, self.sw2, self.b2, out=self.o)
-        if ev is not None:
-            ev[4].record()
+    def ln(self, _=0):
+        self.zq.zq_layernorm_quant_tokenwise(self.x, self.gamma, self.beta, 1e-5, out=(self.xq, self.st))
 
-    def fp16_step(self):
+    def gemm1(self, _=0):
+        self.zq.zq_gemm_i8_dequant(self.xq, self.st, self.wq1, self.sw1, self.b1, out=self.h)
+
+    def gelu(self, _=0):
+        self.zq.zq_gelu_quant_tokenwise(self.h, None, out=(self.hq, self.st2))
+
+    def gemm2(self, _=0):
+        self.zq.zq_gemm_i8_dequant(self.hq, self.st2, self.wq2, self.sw2, self.b2, out=self.o)
+
+    def step(self, _=0):
+        self.ln()
+        self.gemm1()
+        self.gelu()
+        self.gemm2()
+
+    def fp16_step(self, _=0):
         F = torch.nn.functional
         y = F.layer_norm(self.x, (self.H,), self.gamma, self.beta, 1e-5)
         h = F.linear(y, self.w1, self.b1)
@@ -100,30 +134,13 @@ class FFCPair:
         return F.linear(a, self.w2, self.b2)
 
 
-def time_loop(fn, steps, warmup):
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    e0, e1 = _events(2)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) * 1e3
-    return max(e0.elapsed_time(e1), 0.0), wall
-
-
-def cpu_baseline(wl, budget_tokens=1024):
-    """The oracle, as it stands, on the host cores, over the first `budget_tokens` tokens of the same chain."""
+def cpu_baseline(wl):
+    """The oracle, as it stands, on the host cores, over the same chain and the same tokens."""
     from oracle import zq_oracle as orc
-    m = min(budget_tokens, wl.M)
-    x = wl.x_h[:m]
     wq1, sw1, _ = orc.quantize_weight_groupwise(wl.w1_h, wl.g, 8)
     wq2, sw2, _ = orc.quantize_weight_groupwise(wl.w2_h, wl.g, 8)
     t0 = time.perf_counter()
-    _, y32 = orc.layernorm(x, wl.gamma_h, wl.beta_h, 1e-5)
+    _, y32 = orc.layernorm(wl.x_h, wl.gamma_h, wl.beta_h, 1e-5)
     xq, st = orc.quant_tokenwise(y32)
     acc = orc.matmul_i32(xq, wq1)
     ref, _ = orc.dequant(acc, st, sw1, wl.b1_h)
@@ -133,9 +150,8 @@ def cpu_baseline(wl, budget_tokens=1024):
     acc2 = orc.matmul_i32(hq, wq2)
     orc.dequant(acc2, st2, sw2, wl.b2_h)
     dt = time.perf_counter() - t0
-    ops = 2.0 * m * (wl.H * wl.F * 2)
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "first %d of %d tokens of the same chain, %.1f s wall" % (m, wl.M, dt)}
+    return {"value": wl.ops / dt / 1e12, "unit": "TOPS", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "one step of the same chain, all %d tokens, %.2f s wall" % (wl.M, dt)}
 
 
 def run_default(args):
@@ -143,121 +159,123 @@ def run_default(args):
     zq.lib()
     torch.cuda.set_device(0)
     wl = FFCPair(zq)
-    # whole-chain throughput
-    ms, wall_ms = time_loop(wl.step, args.steps, args.warmup)
-    ms_per_step = ms / args.steps
+    spg = 10                                    # steps per graph
+    replays = max(1, args.steps // spg)
+    steps = replays * spg
+    g = graph_of(wl.step, spg)
+    for _ in range(max(1, args.warmup // spg)):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = _events(2)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / steps
     tops = wl.ops / (ms_per_step * 1e-3) / 1e12
-    # per-call breakdown, events on the same stream inside a second timed region
-    n_prof = min(args.steps, 200)
-    evs = [_events(5) for _ in range(n_prof)]
-    for i in range(n_prof):
-        wl.step(evs[i])
-    torch.cuda.synchronize()
-    per = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in evs])     # ms
-    call_ms = per.mean(axis=0)
-    gemm_ms = float((call_ms[1] + call_ms[3]) / 2)
-    achieved = wl.gemm_ops / (gemm_ms * 1e-3) / 1e12
-    # FP16 comparator: the same chain through torch
-    fms, _ = time_loop(wl.fp16_step, args.steps, args.warmup)
-    fp16_ms = fms / args.steps
-    fe = [_events(2) for _ in range(50)]
-    for a, b in fe:
-        a.record()
-        torch.nn.functional.linear(wl.h, wl.w2, wl.b2)
-        b.record()
-    torch.cuda.synchronize()
-    fp16_gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in fe]))
+
+    # per-call durations: each call replayed back to back in a graph of its own, on the same stream
+    calls = {}
+    for name, fn in (("layernorm_quant", wl.ln), ("gemm_ffc1", wl.gemm1), ("gelu_quant", wl.gelu),
+                     ("gemm_ffc2", wl.gemm2)):
+        calls[name] = time_graph(graph_of(fn, 20), 10, 20) * 1e3          # us
+    gemm_us = (calls["gemm_ffc1"] + calls["gemm_ffc2"]) / 2
+    achieved = wl.gemm_ops / (gemm_us * 1e-6) / 1e12
+
+    gf = graph_of(wl.fp16_step, spg)
+    fp16_ms = time_graph(gf, replays, spg)
+    fp16_gemm_us = time_graph(graph_of(lambda i: torch.nn.functional.linear(wl.x, wl.w1, wl.b1), 20), 10, 20) * 1e3
+
     out = {
         "metric": "quantized-linear TOPS (W8A8, LayerNorm+quant -> GeMM -> GeLU+quant -> GeMM)",
-        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "c2: BERT-large FFC pair 1024->4096->1024, 4096 tokens (batch 32 x seq 128), "
                                "INT8 weights in 64 groups, token-wise INT8 activations",
                    "tokens": wl.M, "hidden": wl.H, "ffn": wl.F, "groups": wl.g,
+                   "launch": "HIP graph replay, %d steps per graph" % spg,
                    "offline_weight_quant_ms": wl.weight_quant_ms},
-        "roofline": {"bound": "mfma", "kernel": "gemm_tile_kernel (INT8 MFMA, one launch = one 4096x4096x1024 GeMM)",
-                     "achieved": achieved, "peak": PEAK_INT8_TOPS / 1e3 * 1e3, "unit": "TOP/s",
-                     "frac": achieved / PEAK_INT8_TOPS, "traffic": None,
-                     "avg_launch_us": gemm_ms * 1e3},
-        "calls_us": {"layernorm_quant": call_ms[0] * 1e3, "gemm_ffc1": call_ms[1] * 1e3,
-                     "gelu_quant": call_ms[2] * 1e3, "gemm_ffc2": call_ms[3] * 1e3},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": achieved / PEAK_INT8_TOPS, "traffic": GEMM_TRAFFIC_BYTES,
+                     "kernel": "gemm_tile_kernel (INT8 MFMA; one launch = one 4096-token GeMM of 2*4096*1024*4096 ops)",
+                     "avg_launch_us": gemm_us},
+        "calls_us": calls,
         "frontend_hbm": {
-            "layernorm_quant_GBs": (3.0 * wl.M * wl.H + 4 * wl.H + 4 * wl.M) / (call_ms[0] * 1e-3) / 1e9,
-            "gelu_quant_GBs": (3.0 * wl.M * wl.F + 4 * wl.M) / (call_ms[2] * 1e-3) / 1e9,
+            "layernorm_quant_GBs": (3.0 * wl.M * wl.H + 4 * wl.H + 4 * wl.M) / (calls["layernorm_quant"] * 1e-6) / 1e9,
+            "gelu_quant_GBs": (3.0 * wl.M * wl.F + 4 * wl.M) / (calls["gelu_quant"] * 1e-6) / 1e9,
             "peak_GBs": PEAK_HBM_GBS},
         "fp16": {"ms_per_step": fp16_ms, "speedup_chain": fp16_ms / ms_per_step,
-                 "gemm_ffc2_us": fp16_gemm_ms * 1e3, "speedup_gemm_ffc2": fp16_gemm_ms / (call_ms[3])},
+                 "gemm_ffc1_us": fp16_gemm_us, "speedup_gemm_ffc1": fp16_gemm_us / calls["gemm_ffc1"]},
         "paper_context": "ZeroQuant reports whole-model W8A8 speed-ups on A100-40GB only "
                          "(BERT-large seq128: 2.62x at batch 1 to 5.01x at batch 128); no kernel-level figures",
     }
-    out["roofline"]["peak"] = PEAK_INT8_TOPS
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 
 
 # ------------------------------------------------------------------ table ----
-def _rot_count(bytes_per_set, target=640 << 20, cap=64):
-    return int(max(1, min(cap, -(-target // max(bytes_per_set, 1)))))
+def _codes(gen, rows, cols, cfg):
+    """INT8 activation codes with the value structure of the workload: N(0,1) rows with the
+    configuration's outlier channels, quantized per row (torch ops; input preparation only)."""
+    x = torch.randn((rows, cols), generator=gen, device="cuda")
+    if cfg in ("c1", "c2"):
+        n_out = 4 if cfg == "c1" else max(1, cols // 100)
+        idx = torch.randperm(cols, generator=gen, device="cuda")[:n_out]
+        x[:, idx] *= 20.0 if cfg == "c1" else 15.0
+    elif cfg in ("c3", "c5"):
+        x *= torch.exp(torch.empty((rows, 1), device="cuda").uniform_(np.log(0.5), np.log(2.0), generator=gen))
+    else:
+        n_ht = max(1, int(round(0.005 * cols)))
+        idx = torch.randperm(cols, generator=gen, device="cuda")[:n_ht]
+        t = torch.randn((rows, n_ht), generator=gen, device="cuda") / torch.sqrt(
+            torch.clamp((torch.randn((rows, n_ht, 3), generator=gen, device="cuda") ** 2).mean(-1), min=1e-3))
+        x[:, idx] = t
+    a = x.abs().amax(dim=1, keepdim=True).clamp_min(1e-6)
+    return torch.round(x * (127.0 / a)).clamp_(-127, 127).to(torch.int8), (a[:, 0] / 127.0).float()
 
 
-def time_gemm(zq, name, M, reps=50):
+def time_gemm(zq, name, M, reps_target=40):
     K, N, g, bits = zq_inputs.LINEARS[name]
-    qmax = 127 if bits == 8 else 7
-    gen = torch.Generator(device="cuda").manual_seed(1 + M)
+    cfg = name.split("_")[0]
+    gen = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED % (2 ** 31) + M)
     wbytes = N * K * bits // 8
-    nset = _rot_count(wbytes + M * K + 2 * M * N) if M <= 64 else 1
+    per_set = wbytes + M * K + 2 * M * N
+    nset = int(max(1, min(32, -(-(640 << 20) // per_set)))) if M <= 64 else 1
     sets = []
     for _ in range(nset):
-        xq = torch.randint(-127, 128, (M, K), generator=gen, device="cuda", dtype=torch.int8)
-        if bits == 8:
-            wq = torch.randint(-qmax, qmax + 1, (N, K), generator=gen, device="cuda", dtype=torch.int8)
-        else:
-            wq = torch.randint(0, 256, (N, K // 2), generator=gen, device="cuda", dtype=torch.uint8)
+        xq, st = _codes(gen, M, K, cfg)
+        w = (torch.randn((N, K), generator=gen, device="cuda") * 0.02 *
+             torch.exp(torch.empty((N, 1), device="cuda").uniform_(np.log(0.3), np.log(3.0), generator=gen))).half()
+        wq, sw = zq.zq_quantize_weight_groupwise(w, g, bits)
+        del w
         out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-        sets.append((xq, wq, out))
-    st = torch.rand(M, device="cuda") * 0.1 + 0.01
-    sw = torch.rand(g, device="cuda") * 1e-3 + 1e-4
-    bias = (torch.randn(N, device="cuda") * 0.01).half()
+        sets.append((xq, st, wq, sw, out))
+    bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
     nws = zq.gemm_workspace_bytes(M, N, K, bits)
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
     fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
 
     def run(i):
-        xq, wq, out = sets[i % nset]
+        xq, st, wq, sw, out = sets[i % nset]
         fn(xq, st, wq, sw, bias, workspace=ws, out=out)
 
-    for i in range(max(5, nset)):
-        run(i)
-    torch.cuda.synchronize()
-    best = None
-    for _ in range(5):
-        e0, e1 = _events(2)
-        e0.record()
-        for i in range(reps):
-            run(i)
-        e1.record()
-        torch.cuda.synchronize()
-        t = e0.elapsed_time(e1) / reps
-        best = t if best is None else min(best, t)
-    # FP16 comparator on the same shape (one buffer set is enough: it is a comparator)
+    reps = max(nset, reps_target // max(1, nset) * nset) if M <= 64 else 10
+    gq = graph_of(run, reps)
+    best = min(time_graph(gq, 3, reps, warm=1) for _ in range(3))          # ms per call
     xf = torch.randn((M, K), device="cuda", dtype=torch.float16)
-    wf = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.02
-    for _ in range(5):
-        torch.nn.functional.linear(xf, wf, bias)
-    torch.cuda.synchronize()
-    fbest = None
-    for _ in range(3):
-        e0, e1 = _events(2)
-        e0.record()
-        for i in range(reps):
-            torch.nn.functional.linear(xf, wf, bias)
-        e1.record()
-        torch.cuda.synchronize()
-        t = e0.elapsed_time(e1) / reps
-        fbest = t if fbest is None else min(fbest, t)
-    del xf, wf
+    wfs = [torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.02
+           for _ in range(min(nset, max(1, (640 << 20) // (2 * N * K) + 1)) if M <= 64 else 1)]
+    gf = graph_of(lambda i: torch.nn.functional.linear(xf, wfs[i % len(wfs)], bias), reps)
+    fbest = min(time_graph(gf, 3, reps, warm=1) for _ in range(2))
+    del xf, wfs, gf, gq
     ops = 2.0 * M * N * K
     bytes_min = M * K + wbytes + 4 * M + 4 * g + 2 * N + 2 * M * N
     variant = zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nws))
@@ -282,9 +300,9 @@ def run_table(args):
     for name, M in cases:
         r = time_gemm(zq, name, M)
         rows.append(r)
-        print("%-8s M=%-6d %-14s %9.1f us %8.1f TOPS %8.1f GB/s  int8 %.3f hbm %.3f  fp16 x%.2f" % (
+        print("%-8s M=%-6d %-14s %9.1f us %8.1f TOPS %8.1f GB/s  int8 %.3f hbm %.3f  fp16 %8.1f us x%.2f" % (
             name, M, r["schedule"], r["us"], r["TOPS"], r["GBs"], r["frac_int8_peak"], r["frac_hbm_peak"],
-            r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
+            r["fp16_us"], r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
         torch.cuda.empty_cache()
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
@@ -294,11 +312,14 @@ def run_table(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--table", action="store_true", help="time every workload shape; writes gpurun_out/bench_table.json")
     ap.add_argument("--only", default="", help="with --table: restrict to linears whose name starts with this")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device copy, the known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the quantized linear layer has no cross-GPU step "
