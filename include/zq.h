@@ -151,6 +151,20 @@ int zq_debug_force_gemm_variant(int variant);
 const char *zq_gemm_variant_name(int variant);
 int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes);
 
+/*
+ * How the weight-streaming schedules (M <= 64, K a multiple of 256) cut a
+ * GeMM over the chip (Sec. 4.3: small-batch latency is weight-loading time,
+ * so the cut is made for memory bandwidth): the N/16 strips of 16 weight rows
+ * are dealt evenly over *row_blocks workgroups of *consumers strips at most,
+ * and K is divided over *k_splits workgroups (1 unless a workspace of at
+ * least zq_gemm_workspace_bytes() is offered and the matrix has too few rows
+ * to occupy every CU otherwise).  Host-only; launches nothing.
+ * Returns ZQ_OK, ZQ_ERR_NULL, or ZQ_ERR_UNSUPPORTED for a shape these
+ * schedules do not take.
+ */
+int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t workspace_bytes, int *row_blocks, int *k_splits,
+                        int *consumers);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,6 +7,7 @@ stream.  There is no CPU fallback: a missing library is an error.
 from .binding import (  # noqa: F401
     ZQError,
     gemm_choose_variant,
+    gemm_stream_plan,
     gemm_variant_name,
     gemm_workspace_bytes,
     force_gemm_variant,

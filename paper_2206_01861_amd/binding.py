@@ -16,7 +16,7 @@ _lib = None
 SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
-    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant",
+    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan",
 ]
 
 
@@ -63,6 +63,8 @@ def lib():
     L.zq_gemm_variant_name.argtypes = [ci]
     L.zq_gemm_choose_variant.restype = ci
     L.zq_gemm_choose_variant.argtypes = [ci, ci, ci, ci, sz]
+    L.zq_gemm_stream_plan.restype = ci
+    L.zq_gemm_stream_plan.argtypes = [ci, ci, ci, ci, sz] + [ctypes.POINTER(ci)] * 3
     _lib = L
     return L
 
@@ -106,6 +108,14 @@ def gemm_variant_name(variant):
 
 def gemm_choose_variant(M, N, K, w_bits=8, workspace_bytes=0):
     return lib().zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes)
+
+
+def gemm_stream_plan(M, N, K, w_bits=8, workspace_bytes=0):
+    """(row_blocks, k_splits, consumers) of the weight-streaming schedules for a shape."""
+    rb, ks, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().zq_gemm_stream_plan(M, N, K, w_bits, workspace_bytes, ctypes.byref(rb), ctypes.byref(ks),
+                                     ctypes.byref(c)))
+    return rb.value, ks.value, c.value
 
 
 def zq_quantize_weight_groupwise(w_fp16, groups, bits):

@@ -9,13 +9,12 @@ namespace zq {
 hipError_t launch_gemm_simple(const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st);
 hipError_t launch_gemm_skinny(const GemmArgs &a, bool split_k, hipStream_t st);
-int skinny_splits(int N, int K, int w_bits);
+size_t stream_workspace_bytes(int M, int N, int K, int w_bits);
+void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers);
 
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits) {
-    if (variant != kGemmSkinnySplitK) return 0;
-    const int splits = skinny_splits(N, K, w_bits);
-    if (splits <= 1) return 0;
-    return (size_t)splits * (size_t)M * (size_t)N * sizeof(int32_t);
+    if (variant != kGemmSkinnySplitK || M > 64 || (K % 256) != 0) return 0;
+    return stream_workspace_bytes(M, N, K, w_bits);
 }
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes) {
@@ -63,4 +62,15 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
     if (t256 >= 256) return kGemmTile256;
     return kGemmTile128;
+}
+
+extern "C" int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t workspace_bytes, int *row_blocks,
+                                   int *k_splits, int *consumers) {
+    using namespace zq;
+    if (row_blocks == nullptr || k_splits == nullptr || consumers == nullptr) return ZQ_ERR_NULL;
+    if (M <= 0 || M > 64 || N <= 0 || (N % 16) != 0 || K <= 0 || (K % 256) != 0 || (w_bits != 8 && w_bits != 4))
+        return ZQ_ERR_UNSUPPORTED;
+    const bool split = workspace_bytes > 0 && workspace_bytes >= stream_workspace_bytes(M, N, K, w_bits);
+    stream_plan(M, N, K, w_bits, split, row_blocks, k_splits, consumers);
+    return ZQ_OK;
 }

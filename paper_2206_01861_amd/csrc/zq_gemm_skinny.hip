@@ -4,9 +4,9 @@
 // batch x sequence length).
 //
 // The kernel is bound by HBM, so it is built around bytes in flight.  A
-// workgroup has four consumer waves and one producer wave and owns 64 weight
-// rows (one 16-row strip per consumer) over a slice of K, in stages of 256
-// values of K:
+// workgroup has one producer wave and up to eight consumer waves; each
+// consumer owns one 16-row strip of the weight matrix over the workgroup's
+// range of K, in stages of 256 values of K:
 //   * each consumer streams its own strip straight into registers, DW stages
 //     ahead (16-byte buffer loads; the four loads of a stage cover 256
 //     contiguous bytes of each row).  Registers hold far more outstanding
@@ -23,10 +23,22 @@
 // the activation bytes are permuted the same way and the exact factor 16 is
 // shifted out of the accumulator.
 //
-// When N/64 alone gives too few workgroups, K is split across workgroups:
-// INT32 partial sums go to the caller's workspace and the workgroup that
-// finishes a tile last adds them in split order and applies the epilogue
-// (integer addition, so the result does not depend on timing).
+// Work is cut into row blocks x K splits.  A CU cannot pull more than its share
+// of HBM bandwidth, so an idle or overloaded CU is lost time: the strips are
+// dealt evenly over a number of row blocks that is a multiple of the CU count
+// where N allows it (blocks differ by at most one strip; a wave without a strip
+// only keeps the barriers), and only matrices with too few rows for that are
+// also split along K.  The host picks the cut from a small cost model (bytes
+// per CU, bytes in flight per CU, the fixed cost of the exchange).  With a K
+// split every wave parks its INT32 partial strip in the caller's workspace with
+// device-coherent 16-byte stores and counts its arrival with a relaxed atomic;
+// the wave that arrives last adds the other partials and applies the epilogue
+// (two's-complement addition: the result does not depend on timing).  The
+// protocol is per wave and uses no barrier and no cache-wide fence (on a
+// multi-XCD part a fence flushes and invalidates the L2 every workgroup streams
+// from).
+#include <type_traits>
+
 #include "zq_device.h"
 #include "zq_internal.h"
 
@@ -35,10 +47,10 @@ namespace zq {
 namespace {
 
 constexpr uint32_t kRsrcFlags = 0x00020000u;   // raw 32-bit buffer, gfx9 encoding
-constexpr int kMaxSplitTiles = 8192;
+constexpr int kMaxSharedStrips = 8192;         // arrival counters, one per 16-row strip that is split along K
 constexpr int kStageK = 256;                   // values of K per stage
-constexpr int kAuxDeviceCoherent = 0x10;        // sc1: coherent across the XCDs of the device
-constexpr int kStreamDepth = 4;                // weight stages a consumer keeps in flight
+[[maybe_unused]] constexpr int kAuxDeviceCoherent = 0x10;        // sc1: coherent across the XCDs of the device
+constexpr int kMaxConsumers = 8;               // consumer waves per workgroup
 
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -101,19 +113,25 @@ __device__ __forceinline__ void stream_wait(int32x4 (&w)[LW]) {
 
 }  // namespace
 
-// Arrival counters of the split-K tiles.  Zero when the library is loaded and zero again after
-// every call (the last workgroup of a tile resets its counter), so no launch is spent clearing
-// them.  Shared by all calls on a device: split-K GeMM calls must not overlap on one device.
-__device__ unsigned int g_tile_arrivals[kMaxSplitTiles];
+// Arrival counters of the strips that are split along K.  Zero when the library is loaded and
+// zero again after every call (the wave that completes a strip resets its counter), so no launch
+// is spent clearing them.  Shared by all calls on a device: GeMM calls that split K must not
+// overlap on one device.
+__device__ unsigned int g_strip_arrivals[kMaxSharedStrips];
+
+struct StreamPlan {
+    int strips;       // 16-row strips of the weight matrix (N / 16)
+    int stages;       // stages of 256 K-values (K / 256)
+    int row_blocks;   // workgroups along N; block b owns strips [b*strips/row_blocks, (b+1)*strips/row_blocks)
+    int k_splits;     // workgroups along K; split s owns stages [s*stages/k_splits, (s+1)*stages/k_splits)
+    int consumers;    // consumer waves per workgroup = most strips in a row block
+};
 
 template <int MT, int WBITS, int DW, int R>
-__global__ __launch_bounds__(320) void gemm_stream_kernel(const int8_t *__restrict__ xq,
-                                                          const float *__restrict__ s_tok,
-                                                          const uint8_t *__restrict__ wq,
-                                                          const float *__restrict__ s_w, int gs,
-                                                          const half_t *__restrict__ bias, int M, int N, int K,
-                                                          half_t *__restrict__ out, int32_t *__restrict__ acc_out,
-                                                          int32_t *__restrict__ partial, int stages_per_split) {
+__global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
+    const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
+    const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int32_t *__restrict__ partial, StreamPlan plan) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int LW = (WBITS == 8) ? 4 : 2;          // 16-byte weight loads per lane per stage
@@ -124,14 +142,17 @@ __global__ __launch_bounds__(320) void gemm_stream_kernel(const int8_t *__restri
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int r = lane % 16;
     const int j = lane / 16;
-    const int n0 = blockIdx.x * 64;
-    const int total_stages = K / kStageK;
-    const int st_lo = blockIdx.y * stages_per_split;
-    int st_hi = st_lo + stages_per_split;
-    if (st_hi > total_stages) st_hi = total_stages;
-    const int nst = st_hi - st_lo;
 
-    if (wave == 4) {
+    const int rb = (int)blockIdx.x % plan.row_blocks;
+    const int ks = (int)blockIdx.x / plan.row_blocks;
+    const int s_lo = (int)((long)rb * plan.strips / plan.row_blocks);
+    const int s_hi = (int)(((long)rb + 1) * plan.strips / plan.row_blocks);
+    const int k_lo = (int)((long)ks * plan.stages / plan.k_splits);
+    const int k_hi = (int)(((long)ks + 1) * plan.stages / plan.k_splits);
+    const int n = k_hi - k_lo;                        // stages of this workgroup (>= 1: k_splits <= stages)
+    const int npad = (n + DW - 1) / DW * DW;          // the pipeline always runs whole groups of DW
+
+    if (wave == 0) {
         // ---- producer: activation stages into the LDS ring ------------------
         // A 1 KB unit is 4 rows x 256 bytes; chunk c of row m sits at position c ^ (m & 15),
         // which makes the consumers' fragment reads (16 rows, one chunk) conflict free.
@@ -145,43 +166,47 @@ __global__ __launch_bounds__(320) void gemm_stream_kernel(const int8_t *__restri
             if (grow > M - 1) grow = M - 1;           // rows past M: valid data, results never stored
             voff[u] = grow * K + (((lane % 16) ^ (row & 15)) * 16);
         }
-        auto issue_x = [&](int stage_abs, int slot) {
+        auto issue_x = [&](int i, int slot) __attribute__((always_inline)) {
             uint8_t *base = smem + slot * X_STAGE;
+            const int soff = (k_lo + i) * kStageK;
 #pragma unroll
             for (int u = 0; u < LX; ++u)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[u],
-                                                         stage_abs * kStageK, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[u], soff, 0, 0);
         };
 #pragma unroll
         for (int s = 0; s < R - 1; ++s)
-            if (s < nst) issue_x(st_lo + s, s);
-        for (int kt = 0; kt < nst; ++kt) {
-            // Stage kt has landed once at most the R-2 later stages are outstanding.
-            if (kt + R - 2 < nst)
-                wait_vmcnt<(R - 2) * LX>();
-            else
-                wait_vmcnt<0>();
-            lds_barrier();                            // slot kt filled; slot kt-1 drained by every consumer
-            if (kt + R - 1 < nst) issue_x(st_lo + kt + R - 1, (kt + R - 1) % R);
+            if (s < n) issue_x(s, s);
+        for (int i = 0; i < npad; ++i) {
+            if (i < n) {
+                // Stage i has landed once at most the R-2 later stages are outstanding.
+                if (i + R - 2 < n)
+                    wait_vmcnt<(R - 2) * LX>();
+                else
+                    wait_vmcnt<0>();
+            }
+            lds_barrier();                            // slot i filled; slot i-1 drained by every consumer
+            if (i + R - 1 < n) issue_x(i + R - 1, (i + R - 1) % R);
         }
-        if (gridDim.y > 1) {                          // keep the two barriers of the split-K hand-over balanced
-            lds_barrier();
-            __syncthreads();
-        }
+        return;
+    }
+
+    const int strip = s_lo + wave - 1;
+    if (strip >= s_hi) {                              // no strip for this wave: keep the barrier count
+        for (int i = 0; i < npad; ++i) lds_barrier();
         return;
     }
 
     // ---- consumers: weight strip through registers ------------------------
     const int wrow_bytes = (WBITS == 8) ? K : K / 2;
     const uint32x4 rs_w = make_srd(wq, (uint32_t)((size_t)N * wrow_bytes));
-    int wrow = n0 + wave * 16 + r;
-    if (wrow > N - 1) wrow = N - 1;
-    const int voff_w = wrow * wrow_bytes + j * 16;
     constexpr int W_STAGE_BYTES = (WBITS == 8) ? kStageK : kStageK / 2;   // bytes of a row per stage
+    const int voff_w = (int)((uint32_t)(strip * 16 + r) * (uint32_t)wrow_bytes + (uint32_t)(j * 16));
 
     int32x4 wreg[DW][LW];
-    auto issue_w = [&](int stage_abs, int32x4(&dst)[LW]) {
-        const int soff = stage_abs * W_STAGE_BYTES;
+    // Stage i of this workgroup; indices past the end re-load the last stage (never computed).
+    auto issue_w = [&](int i, int32x4(&dst)[LW]) __attribute__((always_inline)) {
+        if (i > n - 1) i = n - 1;
+        const int soff = __builtin_amdgcn_readfirstlane((k_lo + i) * W_STAGE_BYTES);   // wave-uniform by construction
         stream_load16<0>(dst[0], voff_w, rs_w, soff);
         stream_load16<64>(dst[1], voff_w, rs_w, soff);
         if (LW == 4) {
@@ -195,7 +220,7 @@ __global__ __launch_bounds__(320) void gemm_stream_kernel(const int8_t *__restri
     for (int mt = 0; mt < MT; ++mt) acc[mt] = int32x4{0, 0, 0, 0};
 
     const int x_lane = r * kStageK;                   // this lane's row inside a 16-row block
-    auto compute = [&](const int32x4(&w)[LW], const uint8_t *xs) {
+    auto compute = [&](const int32x4(&w)[LW], const uint8_t *xs) __attribute__((always_inline)) {
         if (WBITS == 8) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {             // k step i: bytes 64i + 16j of the stage
@@ -225,137 +250,172 @@ __global__ __launch_bounds__(320) void gemm_stream_kernel(const int8_t *__restri
         }
     };
 
-    // The slice is processed in groups of DW stages.  Everything on the streamed path is
-    // unconditional, so a register that is the target of a load in flight is never copied or
-    // merged by the compiler: issue group 0; for every further group, step through the stages,
-    // each step waiting for its stage, computing it and refilling the register set it just freed
-    // with the same stage of the next group; finally drain the last group.
-    const int ngroups = nst / DW;
-    int kt = 0;
-    if (ngroups >= 1) {
+    // The run is processed in groups of DW stages.  Everything that touches the streamed registers
+    // is unconditional, so a register that is the target of a load in flight is never copied or
+    // merged by the compiler: issue the first group; then step through the stages, each step
+    // waiting for its stage, computing it (if it exists) and refilling the register set it just
+    // freed with the stage DW further on; the last group only drains.
+    int i = 0;
+    auto step_compute = [&](const int32x4(&w)[LW]) __attribute__((always_inline)) {
+        if (i < n) compute(w, smem + (i % R) * X_STAGE);
+    };
 #pragma unroll
-        for (int d = 0; d < DW; ++d) issue_w(st_lo + d, wreg[d]);
-        for (int g = 1; g < ngroups; ++g) {
+    for (int d = 0; d < DW; ++d) issue_w(d, wreg[d]);
+    for (int grp = DW; grp < npad; grp += DW) {
 #pragma unroll
-            for (int d = 0; d < DW; ++d) {
-                stream_wait<(DW - 1) * LW, LW>(wreg[d]);   // at most DW-1 later stages outstanding
-                lds_barrier();                              // activation slot of stage kt is filled
-                compute(wreg[d], smem + (kt % R) * X_STAGE);
-                issue_w(st_lo + kt + DW, wreg[d]);
-                ++kt;
-            }
+        for (int d = 0; d < DW; ++d) {
+            stream_wait<(DW - 1) * LW, LW>(wreg[d]);   // at most DW-1 later stages outstanding
+            lds_barrier();                              // activation slot of stage i is filled
+            step_compute(wreg[d]);
+            issue_w(i + DW, wreg[d]);
+            ++i;
         }
-        static_assert(DW == 4, "the drain below is written out for four stages");
-#define ZQ_DRAIN(d)                                         \
-    stream_wait<(DW - 1 - (d)) * LW, LW>(wreg[d]);         \
-    lds_barrier();                                          \
-    compute(wreg[d], smem + (kt % R) * X_STAGE);            \
-    ++kt;
-        ZQ_DRAIN(0)
-        ZQ_DRAIN(1)
-        ZQ_DRAIN(2)
-        ZQ_DRAIN(3)
-#undef ZQ_DRAIN
     }
-    // Stages that do not fill a group (K/256 not a multiple of DW, or an uneven split): plain
-    // loads, one stage at a time.
-    for (; kt < nst; ++kt) {
-        const __amdgpu_buffer_rsrc_t rs_plain = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t *>(wq), 0, (int)((size_t)N * wrow_bytes), kRsrcFlags);
-        int32x4 w[LW];
-#pragma unroll
-        for (int i = 0; i < LW; ++i)
-            w[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_plain, voff_w, (st_lo + kt) * W_STAGE_BYTES + i * 64, 0);
-        lds_barrier();
-        compute(w, smem + (kt % R) * X_STAGE);
-    }
+    auto drain = [&](auto dc) __attribute__((always_inline)) {
+        constexpr int d = decltype(dc)::value;
+        if constexpr (d < DW) {
+            stream_wait<(DW - 1 - d) * LW, LW>(wreg[d]);
+            lds_barrier();
+            step_compute(wreg[d]);
+            ++i;
+        }
+    };
+    static_assert(DW <= 8, "the drain is written out for at most eight stages");
+    drain(std::integral_constant<int, 0>{});
+    drain(std::integral_constant<int, 1>{});
+    drain(std::integral_constant<int, 2>{});
+    drain(std::integral_constant<int, 3>{});
+    drain(std::integral_constant<int, 4>{});
+    drain(std::integral_constant<int, 5>{});
+    drain(std::integral_constant<int, 6>{});
+    drain(std::integral_constant<int, 7>{});
 
-    // ---- epilogue ---------------------------------------------------------
-    // One split: dequantize straight from the accumulators.  Several splits: every workgroup
-    // parks its INT32 partial tile in the workspace and bumps the tile's arrival counter; the
-    // workgroup that arrives last adds the partials in split order (integer sums: the result
-    // does not depend on arrival order), dequantizes, and resets the counter for the next call.
-    // The producer wave takes part in the two barriers of the hand-over and then leaves.
     if (WBITS == 4) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[mt][e] >>= 4;   // exact: every product carried the factor 16
     }
-    const int nrow = n0 + wave * 16;
-    const bool row_ok = nrow < N;
-    const int n = nrow + 4 * j;
-    const int splits = gridDim.y;
-    if (splits > 1) {
+
+    // ---- K split: park the partial strip, count the arrival, last arrival adds the others -----
+    if (plan.k_splits > 1) {
+        const int nseg = plan.k_splits;
+        const size_t slot_ints = (size_t)M * 16;      // one strip of one split
         const __amdgpu_buffer_rsrc_t rs_p = __builtin_amdgcn_make_buffer_rsrc(
-            partial, 0, (int)((size_t)splits * M * N * sizeof(int32_t)), kRsrcFlags);
-        if (row_ok) {
+            partial, 0, (int)((size_t)plan.strips * nseg * slot_ints * sizeof(int32_t)), kRsrcFlags);
+        constexpr int kNowhere = 0x7ffffff0;          // past the end of the buffer: stores dropped, loads 0
+        // byte offset of this lane's 16 bytes of row m in the slot of split o
+        auto slot_off = [&](int o, int m) __attribute__((always_inline)) {
+            return (int)((((size_t)strip * nseg + o) * slot_ints + (size_t)m * 16 + 4 * j) * 4);
+        };
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = mt * 16 + r;
-                if (m < M) {
-                    // 16-byte store with the device-coherence bit (sc1): written through, not left in this XCD's L2
-                    __builtin_amdgcn_raw_buffer_store_b128(acc[mt], rs_p, (int)((((size_t)blockIdx.y * M + m) * N + n) * 4),
-                                                           0, kAuxDeviceCoherent);
-                }
-            }
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + r;
+            __builtin_amdgcn_raw_buffer_store_b128(acc[mt], rs_p, (m < M) ? slot_off(ks, m) : kNowhere, 0,
+                                                   kAuxDeviceCoherent);
         }
-        // The partials were written through to device-coherent memory; once every store of this
-        // workgroup is acknowledged the arrival is counted.  No cache-wide fence is used: on a
-        // multi-XCD part it would flush and invalidate the L2 that the other workgroups stream from.
-        wait_vmcnt<0>();
-        lds_barrier();
-        __shared__ int is_last;
-        if (threadIdx.x == 0) {
-            const unsigned prev = __hip_atomic_fetch_add(&g_tile_arrivals[blockIdx.x], 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            is_last = (prev == (unsigned)splits - 1u);
-        }
-        __syncthreads();
-        if (!is_last) return;
-        if (threadIdx.x == 0)
-            __hip_atomic_store(&g_tile_arrivals[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        wait_vmcnt<0>();                              // this wave's partial stores are acknowledged
+        unsigned prev = 0;
+        if (lane == 0)
+            prev = __hip_atomic_fetch_add(&g_strip_arrivals[strip], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __builtin_amdgcn_readfirstlane(prev);
+        if (prev != (unsigned)nseg - 1u) return;
+        if (lane == 0)                                // leave the counter at zero for the next call
+            __hip_atomic_store(&g_strip_arrivals[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int o0 = 0; o0 < nseg; o0 += 4) {        // four partials per round trip
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt] = int32x4{0, 0, 0, 0};
-        if (row_ok) {
-            for (int sp = 0; sp < splits; ++sp) {
+            for (int oo = 0; oo < 4; ++oo) {
+                const int o = o0 + oo;
+                const bool get = o < nseg && o != ks;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int m = mt * 16 + r;
-                    if (m < M) {
-                        acc[mt] += __builtin_amdgcn_raw_buffer_load_b128(
-                            rs_p, (int)((((size_t)sp * M + m) * N + n) * 4), 0, kAuxDeviceCoherent);
-                    }
+                    acc[mt] += __builtin_amdgcn_raw_buffer_load_b128(rs_p, (get && m < M) ? slot_off(o, m) : kNowhere,
+                                                                     0, kAuxDeviceCoherent);
                 }
             }
         }
     }
-    if (!row_ok) return;
+
+    // ---- dequantize this wave's 16 x (MT*16) strip and write it (App. D epilogue) ---------------
+    const int n_col = strip * 16 + 4 * j;
+    const float sw = s_w[n_col / gs];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r;
-        if (m >= M) continue;
-        const int32x4 v = acc[mt];
-        const float sc = s_tok[m] * s_w[n / gs];
-        half4 o;
+        if (m < M) {
+            const float sc = s_tok[m] * sw;
+            half4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float f = (float)v[e] * sc;
-            if (bias != nullptr) f += (float)bias[n + e];
-            o[e] = (half_t)f;
+            for (int e = 0; e < 4; ++e) {
+                float f = (float)acc[mt][e] * sc;
+                if (bias != nullptr) f += (float)bias[n_col + e];
+                o[e] = (half_t)f;
+            }
+            *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
+            if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n_col) = acc[mt];
         }
-        *reinterpret_cast<half4 *>(out + (size_t)m * N + n) = o;
-        if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n) = v;
     }
 #endif
 }
 
 namespace {
 
+constexpr int kCUs = 256;
+
+int token_tiles(int M) { return (M + 15) / 16 > 2 ? 4 : (M + 15) / 16; }
+int stream_depth(int w_bits) { return w_bits == 8 ? 4 : 8; }   // a stage of a strip is 4 KB (INT8) or 2 KB (INT4)
+
+// Choose the cut (row blocks x K splits) with the lowest modelled time.  The model: a CU streams
+// at most kCuRate bytes per microsecond, and no more than its consumers keep in flight over one
+// memory latency; the CU with the most bytes sets the time; activation loads share the CU's load
+// path in proportion to token tiles per consumer; a K split costs the exchange round trips.
+StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
+    const int S = N / 16, St = K / kStageK, mt = token_tiles(M);
+    const double kCuRate = 24e3, kLatency = 2.0, kStart = 4.0, kExchange = 5.0, kExchangeRate = 3e6;
+    const double stage_bytes = 16.0 * kStageK * w_bits / 8;      // one strip, one stage
+    const double inflight = stream_depth(w_bits) * stage_bytes;   // per consumer wave
+    StreamPlan best{S, St, 0, 1, 1};
+    double best_t = 1e30;
+    auto consider = [&](int row_blocks, int k_splits) {
+        if (row_blocks < 1 || row_blocks > S || k_splits < 1 || k_splits > St) return;
+        const int c = (S + row_blocks - 1) / row_blocks;
+        if (c > kMaxConsumers) return;
+        if (k_splits > 1 && (!allow_split || S > kMaxSharedStrips)) return;
+        if ((double)k_splits * M * N * 4.0 >= 2147483648.0) return;   // 32-bit buffer offsets in the exchange
+        const long wgs = (long)row_blocks * k_splits;
+        const int per_cu = (int)((wgs + kCUs - 1) / kCUs);
+        const int st = (St + k_splits - 1) / k_splits;
+        double rate = c * per_cu * inflight / kLatency;
+        if (rate > kCuRate) rate = kCuRate;
+        const double bytes_cu = (double)per_cu * c * st * stage_bytes * (1.0 + 0.3 * mt / c);
+        double t = kStart + bytes_cu / rate;
+        if (k_splits > 1)                           // round trips, then the partials written and read back
+            t += kExchange + 0.25 * ((k_splits + 3) / 4) + 2.0 * k_splits * M * N * 4.0 / kExchangeRate;
+        // near-ties go to the cut that spreads over more CUs
+        const long best_wgs = (long)best.row_blocks * best.k_splits;
+        const bool more_cus = (wgs < kCUs ? wgs : kCUs) > (best_wgs < kCUs ? best_wgs : kCUs);
+        if (t < best_t * 0.99 || (t < best_t * 1.01 && more_cus)) {
+            if (t < best_t) best_t = t;
+            best = StreamPlan{S, St, row_blocks, k_splits, c};
+        }
+    };
+    for (int c = 1; c <= kMaxConsumers; ++c) {
+        const int row_blocks = (S + c - 1) / c;
+        for (int ksp = 1; ksp <= 32; ++ksp) consider(row_blocks, ksp);
+    }
+    for (int m = 1; m <= 8; ++m)
+        for (int ksp = 1; ksp <= 4; ++ksp) consider(kCUs * m / ksp, ksp);   // whole multiples of the CU count
+    if (best.row_blocks == 0) {                       // cannot happen (c = 1, no split is always admissible)
+        best = StreamPlan{S, St, S, 1, 1};
+    }
+    return best;
+}
+
 template <int MT, int WBITS>
-hipError_t launch_stream_t(const GemmArgs &a, int splits, int stages_per_split, hipStream_t st) {
-    constexpr int DW = kStreamDepth;
+hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_t st) {
     constexpr int R = 3;
+    constexpr int DW = (WBITS == 8) ? 4 : 8;
     constexpr size_t lds = (size_t)R * MT * 16 * kStageK;
     static bool attr_set = false;
     if (!attr_set) {
@@ -364,40 +424,35 @@ hipError_t launch_stream_t(const GemmArgs &a, int splits, int stages_per_split, 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const dim3 grid((a.N + 63) / 64, splits);
-    int32_t *partial = splits > 1 ? reinterpret_cast<int32_t *>(a.workspace) : nullptr;
-    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), grid, dim3(320), lds, st, a.xq, a.s_tok,
-                       reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
-                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
-                       a.acc_out, partial, stages_per_split);
+    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks * plan.k_splits),
+                       dim3(64 * (plan.consumers + 1)), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq),
+                       a.s_w, a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
+                       reinterpret_cast<half_t *>(a.out), a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// Number of K splits for the streaming schedule: about one and a half workgroups per CU (more
-// splits cost a round trip of INT32 partials for nothing), never fewer than four stages per split.
-int skinny_splits(int N, int K, int w_bits) {
-    (void)w_bits;
-    const int stages = K / kStageK;
-    const int tiles = (N + 63) / 64;
-    if (tiles > kMaxSplitTiles) return 1;
-    int s = (384 + tiles / 2) / tiles;
-    if (s > stages / 4) s = stages / 4;
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    while (s > 1 && (size_t)s * 64 * (size_t)N * sizeof(int32_t) >= ((size_t)1 << 31)) --s;   // 32-bit offsets
-    return s;
+// Workspace of the K-split schedule: one INT32 partial of M x N per split.  0 when the chosen cut
+// has no K split.
+size_t stream_workspace_bytes(int M, int N, int K, int w_bits) {
+    if (K / kStageK < 1) return 0;
+    const StreamPlan plan = plan_stream(M, N, K, w_bits, true);
+    if (plan.k_splits <= 1) return 0;
+    return (size_t)plan.k_splits * M * N * sizeof(int32_t);
 }
 
-hipError_t launch_gemm_skinny(const GemmArgs &a, bool split_k, hipStream_t st) {
-    const int stages = a.K / kStageK;
-    int splits = split_k ? skinny_splits(a.N, a.K, a.w_bits) : 1;
-    int sps = (stages + splits - 1) / splits;
-    if (splits > 1) sps = (sps + kStreamDepth - 1) / kStreamDepth * kStreamDepth;   // whole groups per split
-    splits = (stages + sps - 1) / sps;            // no empty split
-    const int mt = (a.M + 15) / 16;
-#define ZQ_SK(MT, WB) return launch_stream_t<MT, WB>(a, splits, sps, st)
+void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers) {
+    const StreamPlan plan = plan_stream(M, N, K, w_bits, allow_split);
+    *row_blocks = plan.row_blocks;
+    *k_splits = plan.k_splits;
+    *consumers = plan.consumers;
+}
+
+hipError_t launch_gemm_skinny(const GemmArgs &a, bool allow_split, hipStream_t st) {
+    const StreamPlan plan = plan_stream(a.M, a.N, a.K, a.w_bits, allow_split);
+    const int mt = token_tiles(a.M);
+#define ZQ_SK(MT, WB) return launch_stream_t<MT, WB>(a, plan, st)
     if (a.w_bits == 8) {
         if (mt <= 1) ZQ_SK(1, 8);
         if (mt <= 2) ZQ_SK(2, 8);

@@ -53,6 +53,32 @@ def test_variant_table():
     assert zq.gemm_workspace_bytes(4096, 4096, 1024) == 0
 
 
+def test_stream_plan_covers_the_matrix():
+    """The cut of the weight-streaming schedules: every strip has a consumer wave, no split
+    is empty, a K split is only planned when the offered workspace holds its partials."""
+    import random
+    rnd = random.Random(7)
+    shapes = [(64, 6144, 24576, 8), (16, 4096, 16384, 4), (1, 768, 768, 8), (64, 18432, 6144, 8),
+              (16, 196608, 4096, 4), (7, 16, 256, 8), (64, 131072, 256, 8)]
+    for _ in range(200):
+        shapes.append((rnd.randint(1, 64), 16 * rnd.randint(1, 3000), 256 * rnd.randint(1, 100), rnd.choice([4, 8])))
+    for M, N, K, bits in shapes:
+        ws = zq.gemm_workspace_bytes(M, N, K, bits)
+        for offered in (0, ws):
+            rb, ks, c = zq.gemm_stream_plan(M, N, K, bits, offered)
+            strips, stages = N // 16, K // 256
+            assert 1 <= rb <= strips and 1 <= ks <= stages and 1 <= c <= 8
+            assert c == -(-strips // rb)                  # the fullest row block fits the workgroup
+            if offered == 0:
+                assert ks == 1
+            else:
+                assert ks > 1 and ws == ks * M * N * 4 and strips <= 8192
+    with pytest.raises(zq.ZQError):
+        zq.gemm_stream_plan(65, 1024, 1024)
+    with pytest.raises(zq.ZQError):
+        zq.gemm_stream_plan(8, 1024, 1000)
+
+
 def test_weight_quant_validation():
     f = zq.lib().zq_quantize_weight_groupwise
     assert f(None, 64, 64, 4, 8, P, P, None) == E_NULL
