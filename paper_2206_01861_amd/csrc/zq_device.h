@@ -34,13 +34,25 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return v;
 }
 
-// The symmetric quantizer of App. A.2 for one value: v * inv, rounded half to
-// even (v_rndne_f32), clamped to +-qmax.  One fp32 multiply, no fused add.
-__device__ __forceinline__ int quant_code(float v, float inv, float qmax) {
-    float t = v * inv;
-    float r = rintf(t);
-    r = fminf(fmaxf(r, -qmax), qmax);
-    return (int)r;
+// The symmetric quantizer of App. A.2 for one value: fl32(v * inv) rounded half to even.  The
+// rounding is done by adding 1.5 * 2^23: the sum is rounded to an integer by the adder (round to
+// nearest even, the same rounding as v_rndne_f32) and its low mantissa bits hold that integer in
+// two's complement, so the code is the low byte of the result and no float->int conversion is
+// needed.  No clamp: |v| <= absmax of its block and inv = fl32(qmax / absmax), so
+// |fl32(v * inv)| <= qmax * (1 + 2^-23) and rounds to at most qmax.  The product and the sum
+// stay two separately rounded operations (no fused multiply-add), as the definition has them.
+__device__ __forceinline__ uint32_t quant_code_bits(float v, float inv) {
+#pragma clang fp contract(off)
+    const float t = v * inv;
+    const float r = t + 12582912.0f;
+    return __float_as_uint(r);
+}
+
+// Low bytes of four quant_code_bits() results -> one dword, first value in the low byte.
+__device__ __forceinline__ uint32_t pack4_code_bits(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);   // a.b0, b.b0, 0, 0
+    const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 // scale = fl32(a / qmax), inv = fl32(qmax / a); an all-zero block gets 0 / 0.

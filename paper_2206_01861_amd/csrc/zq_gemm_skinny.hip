@@ -372,7 +372,11 @@ int stream_depth(int w_bits) { return w_bits == 8 ? 4 : 8; }   // a stage of a s
 // path in proportion to token tiles per consumer; a K split costs the exchange round trips.
 StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     const int S = N / 16, St = K / kStageK, mt = token_tiles(M);
-    const double kCuRate = 24e3, kLatency = 2.0, kStart = 4.0, kExchange = 5.0, kExchangeRate = 3e6;
+    const double kCuRate = 24e3, kStart = 4.0, kExchange = 4.5, kExchangeRate = 3e6;
+    // memory latency in microseconds: about 1 on a quiet chip, 2 with 32 MB streaming, 4 beyond 80 MB
+    // (fitted to measured bandwidth against waves per CU)
+    double latency = 1.0 + ((double)N * K * w_bits / 8 / 1048576.0 - 8.0) / 24.0;
+    latency = latency < 1.0 ? 1.0 : (latency > 4.0 ? 4.0 : latency);
     const double stage_bytes = 16.0 * kStageK * w_bits / 8;      // one strip, one stage
     const double inflight = stream_depth(w_bits) * stage_bytes;   // per consumer wave
     StreamPlan best{S, St, 0, 1, 1};
@@ -386,12 +390,12 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
         const long wgs = (long)row_blocks * k_splits;
         const int per_cu = (int)((wgs + kCUs - 1) / kCUs);
         const int st = (St + k_splits - 1) / k_splits;
-        double rate = c * per_cu * inflight / kLatency;
+        double rate = c * per_cu * inflight / latency;
         if (rate > kCuRate) rate = kCuRate;
         const double bytes_cu = (double)per_cu * c * st * stage_bytes * (1.0 + 0.3 * mt / c);
         double t = kStart + bytes_cu / rate;
         if (k_splits > 1)                           // round trips, then the partials written and read back
-            t += kExchange + 0.25 * ((k_splits + 3) / 4) + 2.0 * k_splits * M * N * 4.0 / kExchangeRate;
+            t += kExchange + 0.3 * k_splits + 2.0 * k_splits * M * N * 4.0 / kExchangeRate;
         // near-ties go to the cut that spreads over more CUs
         const long best_wgs = (long)best.row_blocks * best.k_splits;
         const bool more_cus = (wgs < kCUs ? wgs : kCUs) > (best_wgs < kCUs ? best_wgs : kCUs);

@@ -42,22 +42,22 @@ __device__ __forceinline__ float row_max(float v, float *lds) {
     return v;
 }
 
-// GeLU, erf form: u * Phi(u) with Phi from the rational erfc approximation of
-// Abramowitz & Stegun 7.1.26 (absolute error of erf below 1.5e-7, i.e. below
-// fp32 resolution of Phi), evaluated as 0.5 * erfc(|u|/sqrt2) so that the tail
-// keeps its relative accuracy.  About a third of the VALU work of the library
-// erff, which otherwise makes this memory-bound kernel compute-bound.
+// GeLU, erf form: u * Phi(u) = max(u, 0) - |u| * h with h = erfc(|u| / sqrt2) / 2 from the rational
+// approximation of Abramowitz & Stegun 7.1.26 (absolute error of erf below 1.5e-7, i.e. below fp32
+// resolution of Phi); going through erfc keeps the relative accuracy of the negative tail.  The
+// constants carry the factors 1/sqrt2, 1/2 and log2(e).  About a third of the VALU work of the
+// library erff, which otherwise makes this memory-bound kernel compute-bound.
 __device__ __forceinline__ float gelu_erf(float u) {
-    const float z = fabsf(u) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-    float p = fmaf(t, 1.061405429f, -1.453152027f);
-    p = fmaf(t, p, 1.421413741f);
-    p = fmaf(t, p, -0.284496736f);
-    p = fmaf(t, p, 0.254829592f);
-    const float e = __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);
-    const float half_erfc = 0.5f * (p * t) * e;
-    const float phi = (u >= 0.0f) ? 1.0f - half_erfc : half_erfc;
-    return u * phi;
+    const float a = fabsf(u);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, a, 1.0f));
+    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    p = fmaf(t, p, 0.5f * 1.421413741f);
+    p = fmaf(t, p, 0.5f * -0.284496736f);
+    p = fmaf(t, p, 0.5f * 0.254829592f);
+    const float w = u * 0.84932180028801904272f;      // sqrt(log2(e) / 2): exp(-u^2 / 2) = 2^(-w^2)
+    const float e = __builtin_amdgcn_exp2f(-(w * w));
+    const float h = (p * t) * e;
+    return fmaf(-a, h, __builtin_amdgcn_fmed3f(u, 0.0f, __builtin_inff()));   // max(u, 0) in one instruction
 }
 
 // GeLU, tanh form: 0.5 u (1 + tanh(v)) = u * (1 - 1 / (1 + exp(2v))).
@@ -174,10 +174,10 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
                     reinterpret_cast<half8 *>(reinterpret_cast<half_t *>(y_out) + (size_t)row * K)[idx] = h;
                 }
             }
-            int q[8];
+            uint32_t q[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) q[e] = quant_code(v[i][e], inv, 127.0f);
-            rq[idx] = make_uint2(pack4_i8(q[0], q[1], q[2], q[3]), pack4_i8(q[4], q[5], q[6], q[7]));
+            for (int e = 0; e < 8; ++e) q[e] = quant_code_bits(v[i][e], inv);
+            rq[idx] = make_uint2(pack4_code_bits(q[0], q[1], q[2], q[3]), pack4_code_bits(q[4], q[5], q[6], q[7]));
         }
     }
 }
@@ -285,16 +285,16 @@ __global__ __launch_bounds__(256) void wq_quant_kernel(const half8 *__restrict__
     const long gbase = (long)g * chunk_vecs;
     for (long i = lo + threadIdx.x; i < hi; i += 256) {
         half8 h = w[gbase + i];
-        int q[8];
+        uint32_t q[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) q[e] = quant_code((float)h[e], inv, qmax);
+        for (int e = 0; e < 8; ++e) q[e] = quant_code_bits((float)h[e], inv);
         if (BITS == 8) {
             reinterpret_cast<uint2 *>(wq)[gbase + i] =
-                make_uint2(pack4_i8(q[0], q[1], q[2], q[3]), pack4_i8(q[4], q[5], q[6], q[7]));
+                make_uint2(pack4_code_bits(q[0], q[1], q[2], q[3]), pack4_code_bits(q[4], q[5], q[6], q[7]));
         } else {
             uint32_t p = 0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p |= ((uint32_t)q[e] & 0xfu) << (4 * e);   // even k in the low nibble
+            for (int e = 0; e < 8; ++e) p |= (q[e] & 0xfu) << (4 * e);   // even k in the low nibble
             reinterpret_cast<uint32_t *>(wq)[gbase + i] = p;
         }
     }
