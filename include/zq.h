@@ -152,7 +152,7 @@ const char *zq_gemm_variant_name(int variant);
 int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes);
 
 /*
- * How the weight-streaming schedules (M <= 64, K a multiple of 256) cut a
+ * How the weight-streaming schedules (M <= 128, K a multiple of 256) cut a
  * GeMM over the chip (Sec. 4.3: small-batch latency is weight-loading time,
  * so the cut is made for memory bandwidth): the N/16 strips of 16 weight rows
  * are dealt evenly over *row_blocks workgroups of *consumers strips at most,

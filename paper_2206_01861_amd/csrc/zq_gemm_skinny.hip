@@ -1,4 +1,4 @@
-// Weight-streaming GeMM for small token counts (M <= 64), with the
+// Weight-streaming GeMM for small token counts (M <= 128), with the
 // dequantization epilogue (Sec. 4.3: at small batch the latency is the time to
 // load the weights from memory; App. D: the schedule is chosen from
 // batch x sequence length).
@@ -363,7 +363,10 @@ namespace {
 
 constexpr int kCUs = 256;
 
-int token_tiles(int M) { return (M + 15) / 16 > 2 ? 4 : (M + 15) / 16; }
+int token_tiles(int M) {                          // 16-row token tiles held per consumer: 1, 2, 4 or 8
+    const int t = (M + 15) / 16;
+    return t > 4 ? 8 : (t > 2 ? 4 : t);
+}
 int stream_depth(int w_bits) { return w_bits == 8 ? 4 : 8; }   // a stage of a strip is 4 KB (INT8) or 2 KB (INT4)
 
 // Choose the cut (row blocks x K splits) with the lowest modelled time.  The model: a CU streams
@@ -460,11 +463,13 @@ hipError_t launch_gemm_skinny(const GemmArgs &a, bool allow_split, hipStream_t s
     if (a.w_bits == 8) {
         if (mt <= 1) ZQ_SK(1, 8);
         if (mt <= 2) ZQ_SK(2, 8);
-        ZQ_SK(4, 8);
+        if (mt <= 4) ZQ_SK(4, 8);
+        ZQ_SK(8, 8);
     } else {
         if (mt <= 1) ZQ_SK(1, 4);
         if (mt <= 2) ZQ_SK(2, 4);
-        ZQ_SK(4, 4);
+        if (mt <= 4) ZQ_SK(4, 4);
+        ZQ_SK(8, 4);
     }
 #undef ZQ_SK
 }

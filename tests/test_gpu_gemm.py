@@ -73,13 +73,15 @@ SHAPES = [
     (SKINNY, 1, 64, 256, 4), (SKINNY, 3, 128, 768, 8), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
     (SKINNY, 16, 208, 1280, 13), (SKINNY, 17, 80, 512, 5), (SKINNY, 32, 2048, 2048, 128),
     (SKINNY, 33, 144, 1792, 9), (SKINNY, 64, 1024, 1536, 64), (SKINNY, 50, 16, 256, 1),
+    # five to eight token tiles per consumer
+    (SKINNY, 65, 256, 512, 16), (SKINNY, 100, 768, 768, 48), (SKINNY, 128, 2048, 2048, 128), (SKINNY, 113, 144, 1792, 9),
     # strips dealt unevenly over the row blocks, up to eight consumer waves per workgroup
     (SKINNY, 64, 18432, 1024, 128), (SKINNY, 16, 33040, 512, 5), (SKINNY, 9, 4112, 768, 1),
     # K split 3- to 12-fold, with ragged strip counts
     (SKINNY_SPLITK, 1, 2048, 8192, 128), (SKINNY_SPLITK, 8, 256, 4096, 16), (SKINNY_SPLITK, 32, 2048, 8192, 128),
     (SKINNY_SPLITK, 64, 1024, 6144, 64), (SKINNY_SPLITK, 13, 80, 2304, 5), (SKINNY_SPLITK, 33, 2064, 8192, 3),
     (SKINNY_SPLITK, 20, 1040, 12288, 65), (SKINNY_SPLITK, 7, 528, 24576, 11), (SKINNY_SPLITK, 64, 4112, 16384, 1),
-    (SKINNY_SPLITK, 16, 4096, 16384, 256),
+    (SKINNY_SPLITK, 16, 4096, 16384, 256), (SKINNY_SPLITK, 128, 2048, 8192, 128), (SKINNY_SPLITK, 90, 1040, 12288, 65),
 ]
 
 
