@@ -210,6 +210,23 @@ void zq_oracle_gelu(const uint16_t *h, const uint16_t *bias, int approx_tanh,
     }
 }
 
+/* ---- GeLU of fp64 values (the activation of Sec. 4.3's fused bias-add + GeLU,
+ * applied to an already dequantized pre-activation) ------------------------- */
+/* u fp64 [n] -> y fp64 [n]; approx_tanh selects the tanh form. */
+void zq_oracle_gelu_f64(const double *u, int approx_tanh, long n, double *y)
+{
+    const double inv_sqrt2 = 0.70710678118654752440;
+    const double sqrt_2_over_pi = 0.79788456080286535588;
+    #pragma omp parallel for schedule(static)
+    for (long i = 0; i < n; ++i) {
+        const double v = u[i];
+        if (approx_tanh)
+            y[i] = 0.5 * v * (1.0 + tanh(sqrt_2_over_pi * (v + 0.044715 * v * v * v)));
+        else
+            y[i] = 0.5 * v * (1.0 + erf(v * inv_sqrt2));
+    }
+}
+
 /* ---- exact integer GeMM (Sec. 4.3 / App. D) ------------------------------ */
 /* acc[m,n] = sum_k xq[m,k] * wq[n,k], int32 accumulation. */
 void zq_oracle_matmul_i32(const int8_t *xq, const int8_t *wq,

@@ -135,6 +135,14 @@ def gelu(h16, bias16, approx_tanh=False):
     return y64, y32
 
 
+def gelu_f64(u64, approx_tanh=False):
+    """GeLU of fp64 values (any shape) -> fp64."""
+    u64 = _c(u64, np.float64)
+    y = np.empty_like(u64)
+    _load().zq_oracle_gelu_f64(_p(u64), ctypes.c_int(1 if approx_tanh else 0), ctypes.c_long(u64.size), _p(y))
+    return y
+
+
 def matmul_i32(xq, wq):
     """acc[m,n] = sum_k xq[m,k]*wq[n,k] in int32."""
     xq = _c(xq, np.int8)

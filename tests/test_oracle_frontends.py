@@ -68,3 +68,23 @@ def test_gelu_closed_forms():
     assert abs(y64[0, 1] - phi1) < 1e-15
     assert abs(y64[0, 2] + (1 - phi1)) < 1e-15
     assert abs(y64[0, 3] - 8.0) < 1e-12 and abs(y64[0, 4]) < 1e-12
+
+
+def test_gelu_f64_pins():
+    """GeLU on fp64 inputs: the library's float64 GeLU, the identity gelu(x) - gelu(-x) = x
+    (Phi(x) + Phi(-x) = 1; tanh is odd), closed values, and agreement with the FP16-input routine."""
+    rng = zq_inputs.rng_for(7, 5)
+    u = 5 * rng.standard_normal((7, 33))
+    for approx in (False, True):
+        y = orc.gelu_f64(u, approx)
+        want = torch.nn.functional.gelu(torch.from_numpy(u), approximate="tanh" if approx else "none").numpy()
+        assert np.abs(y - want).max() <= 1e-13
+        assert np.abs(y - orc.gelu_f64(-u, approx) - u).max() <= 1e-13
+    phi1 = 0.5 * (1 + math.erf(1 / math.sqrt(2)))
+    y = orc.gelu_f64(np.array([0.0, 1.0, -1.0, 40.0, -40.0]))
+    assert y[0] == 0.0 and abs(y[1] - phi1) < 1e-15 and abs(y[2] + (1 - phi1)) < 1e-15
+    assert y[3] == 40.0 and y[4] == 0.0
+    h = (4 * rng.standard_normal((5, 48))).astype(np.float16)
+    y64, _ = orc.gelu(h, None)
+    assert np.array_equal(orc.gelu_f64(h.astype(np.float64)), y64)
+    assert np.abs(orc.gelu_f64(u, True) - orc.gelu_f64(u, False)).max() > 1e-5
