@@ -138,6 +138,29 @@ zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8
                                void *workspace, size_t workspace_bytes, zq_stream stream);
 
 /*
+ * First feed-forward GeMM with the activation in its epilogue (Sec. 4.3 and
+ * App. D fuse bias-add + GeLU with the token-wise quantization that feeds the
+ * second GeMM; here the bias-add and the GeLU move one step earlier, into the
+ * dequantization epilogue of the first GeMM, so the activation tensor is
+ * written once, already activated):
+ *   g[m,n]    = fp16( GeLU( acc[m,n] * s_tok[m] * s_w[n / (N/groups)] + bias[n] ) )
+ *   (gq, s')  = token-wise INT8 quantization (App. A.2, per row of g) of g as stored in FP16
+ * GeLU is evaluated in fp32 on the unrounded dequantized value (erf form, or
+ * the tanh form when approx_tanh = 1), which differs from the two-call chain
+ * zq_gemm_*_dequant -> zq_gelu_quant_tokenwise only by that one FP16 rounding
+ * of the pre-activation.  The INT32 accumulator is not exported.
+ *   xq, s_tok, s_w, groups, bias_fp16, M, N, K, workspace: as zq_gemm_i8_dequant
+ *   wq        w_bits = 8: int8 [N,K];  w_bits = 4: packed uint8 [N,K/2]   (device)
+ *   g_fp16    out, fp16 [M,N]: the activated tensor (device, required)
+ *   gq_out    out, int8 [M,N];  s_tok_out  out, fp32 [M]                  (device, required)
+ * N <= 32768 (a row of g is quantized from registers).  Errors as the GeMM calls.
+ */
+zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, const void *wq, int w_bits,
+                                       const float *s_w, int groups, const void *bias_fp16, int approx_tanh, int M,
+                                       int N, int K, void *g_fp16, int8_t *gq_out, float *s_tok_out,
+                                       void *workspace, size_t workspace_bytes, zq_stream stream);
+
+/*
  * Tuning and test hook: force the GeMM schedule instead of choosing it from
  * the shape (App. D picks a schedule by batch x sequence length).
  * variant < 0 restores automatic choice.  A forced schedule whose shape

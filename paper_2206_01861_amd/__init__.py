@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     lib_path,
     version,
     zq_gelu_quant_tokenwise,
+    zq_gemm_gelu_quant_tokenwise,
     zq_gemm_i8_dequant,
     zq_gemm_w4a8_dequant,
     zq_layernorm_quant_tokenwise,

@@ -16,7 +16,7 @@ _lib = None
 SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
-    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan",
+    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise",
 ]
 
 
@@ -57,6 +57,8 @@ def lib():
     L.zq_gemm_i8_dequant.argtypes = gemm_args
     L.zq_gemm_w4a8_dequant.restype = ci
     L.zq_gemm_w4a8_dequant.argtypes = gemm_args
+    L.zq_gemm_gelu_quant_tokenwise.restype = ci
+    L.zq_gemm_gelu_quant_tokenwise.argtypes = [vp, vp, vp, ci, vp, ci, vp, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     L.zq_debug_force_gemm_variant.restype = ci
     L.zq_debug_force_gemm_variant.argtypes = [ci]
     L.zq_gemm_variant_name.restype = ctypes.c_char_p
@@ -207,3 +209,37 @@ def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, re
         raise ValueError("wq4 must be [N, K/2]")
     return _gemm(lib().zq_gemm_w4a8_dequant, torch.uint8, xq, s_tok, wq4, s_w, bias_fp16, want_acc, requant,
                  workspace, out)
+
+
+def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh=False, workspace=None, out=None):
+    """GeMM with bias + GeLU in its epilogue, then token-wise INT8 quantization of the FP16 result.
+
+    wq int8 [N,K] or INT4-packed uint8 [N,K/2].  -> (g fp16 [M,N], gq int8 [M,N], s_tok fp32 [M]);
+    `out` = (g, gq, s) reuses caller tensors.
+    """
+    _dev(xq, torch.int8, "xq")
+    _dev(s_tok, torch.float32, "s_tok")
+    _dev(s_w, torch.float32, "s_w")
+    if wq.dtype == torch.int8:
+        w_bits = 8
+    elif wq.dtype == torch.uint8:
+        w_bits = 4
+        if wq.shape[1] * 2 != xq.shape[1]:
+            raise ValueError("wq4 must be [N, K/2]")
+    else:
+        raise TypeError("wq must be int8 (INT8) or uint8 (packed INT4)")
+    _dev(wq, wq.dtype, "wq")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, K = xq.shape
+    N = wq.shape[0]
+    dev = xq.device
+    g, gq, s = out if out is not None else (
+        torch.empty((M, N), dtype=torch.float16, device=dev),
+        torch.empty((M, N), dtype=torch.int8, device=dev),
+        torch.empty(M, dtype=torch.float32, device=dev))
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().zq_gemm_gelu_quant_tokenwise(_ptr(xq), _ptr(s_tok), _ptr(wq), w_bits, _ptr(s_w), int(s_w.numel()),
+                                              _ptr(bias_fp16), 1 if approx_tanh else 0, M, N, K, _ptr(g), _ptr(gq),
+                                              _ptr(s), _ptr(workspace), ws_bytes, _stream()))
+    return g, gq, s

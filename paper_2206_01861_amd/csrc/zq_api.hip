@@ -26,7 +26,8 @@ zq_status check_rowquant(const void *in, const void *p0, const void *p1, int M, 
 
 zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, const float *s_w, int groups,
                       const void *bias, int M, int N, int K, void *out, int32_t *acc_out, int8_t *out_q,
-                      float *out_s_tok, void *workspace, size_t workspace_bytes, int w_bits, zq_stream stream) {
+                      float *out_s_tok, void *workspace, size_t workspace_bytes, int w_bits, int act,
+                      zq_stream stream) {
     if (xq == nullptr || s_tok == nullptr || wq == nullptr || s_w == nullptr || out == nullptr) return ZQ_ERR_NULL;
     if ((out_q == nullptr) != (out_s_tok == nullptr)) return ZQ_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
@@ -48,7 +49,7 @@ zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, cons
     zq::GemmArgs a;
     a.xq = xq; a.s_tok = s_tok; a.wq = wq; a.s_w = s_w; a.groups = groups; a.bias = bias;
     a.M = M; a.N = N; a.K = K; a.out = out; a.acc_out = acc_out;
-    a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.w_bits = w_bits;
+    a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.w_bits = w_bits; a.act = act;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (zq::launch_gemm(variant, a, st) != hipSuccess) return ZQ_ERR_HIP;
     if (out_q != nullptr) {
@@ -129,7 +130,7 @@ zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t 
                              int8_t *out_q, float *out_s_tok, void *workspace, size_t workspace_bytes,
                              zq_stream stream) {
     return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
-                       workspace, workspace_bytes, 8, stream);
+                       workspace, workspace_bytes, 8, 0, stream);
 }
 
 zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8_t *wq4, const float *s_w,
@@ -137,7 +138,18 @@ zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8
                                int32_t *acc_out, int8_t *out_q, float *out_s_tok, void *workspace,
                                size_t workspace_bytes, zq_stream stream) {
     return gemm_common(xq, s_tok, wq4, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
-                       workspace, workspace_bytes, 4, stream);
+                       workspace, workspace_bytes, 4, 0, stream);
+}
+
+zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, const void *wq, int w_bits,
+                                       const float *s_w, int groups, const void *bias_fp16, int approx_tanh, int M,
+                                       int N, int K, void *g_fp16, int8_t *gq_out, float *s_tok_out,
+                                       void *workspace, size_t workspace_bytes, zq_stream stream) {
+    if (w_bits != 8 && w_bits != 4) return ZQ_ERR_UNSUPPORTED;
+    if (approx_tanh != 0 && approx_tanh != 1) return ZQ_ERR_UNSUPPORTED;
+    if (gq_out == nullptr || s_tok_out == nullptr) return ZQ_ERR_NULL;
+    return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, g_fp16, nullptr, gq_out, s_tok_out, workspace,
+                       workspace_bytes, w_bits, approx_tanh ? 2 : 1, stream);
 }
 
 int zq_debug_force_gemm_variant(int variant) {

@@ -23,7 +23,7 @@ template <int WBITS>
 __global__ __launch_bounds__(256) void gemm_simple_kernel(const int8_t *__restrict__ xq, const float *__restrict__ s_tok,
                                                           const uint8_t *__restrict__ wq, const float *__restrict__ s_w,
                                                           int gs, const half_t *__restrict__ bias, int M, int N, int K,
-                                                          half_t *__restrict__ out, int32_t *__restrict__ acc_out) {
+                                                          half_t *__restrict__ out, int32_t *__restrict__ acc_out, int act) {
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int n0 = (blockIdx.x * 4 + wave) * 16;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const int8_t *__restri
     for (int v = 0; v < 4; ++v) {
         float f = (float)acc[v] * sc;
         if (bias != nullptr) f += (float)bias[n + v];
-        o[v] = (half_t)f;
+        o[v] = (half_t)apply_activation(f, act);
     }
     *reinterpret_cast<half4 *>(out + (size_t)m * N + n) = o;
     if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n) = acc;
@@ -81,12 +81,12 @@ hipError_t launch_gemm_simple(const GemmArgs &a, hipStream_t st) {
         hipLaunchKernelGGL(gemm_simple_kernel<8>, grid, dim3(256), 0, st, a.xq, a.s_tok,
                            reinterpret_cast<const uint8_t *>(a.wq), a.s_w, gs,
                            reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                           reinterpret_cast<half_t *>(a.out), a.acc_out);
+                           reinterpret_cast<half_t *>(a.out), a.acc_out, a.act);
     else
         hipLaunchKernelGGL(gemm_simple_kernel<4>, grid, dim3(256), 0, st, a.xq, a.s_tok,
                            reinterpret_cast<const uint8_t *>(a.wq), a.s_w, gs,
                            reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                           reinterpret_cast<half_t *>(a.out), a.acc_out);
+                           reinterpret_cast<half_t *>(a.out), a.acc_out, a.act);
     return hipGetLastError();
 }
 

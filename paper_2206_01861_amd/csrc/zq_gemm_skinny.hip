@@ -131,7 +131,8 @@ template <int MT, int WBITS, int DW, int R>
 __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
-    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int32_t *__restrict__ partial, StreamPlan plan) {
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int32_t *__restrict__ partial, StreamPlan plan,
+    int act) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int LW = (WBITS == 8) ? 4 : 2;          // 16-byte weight loads per lane per stage
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
             for (int e = 0; e < 4; ++e) {
                 float f = (float)acc[mt][e] * sc;
                 if (bias != nullptr) f += (float)bias[n_col + e];
-                o[e] = (half_t)f;
+                o[e] = (half_t)apply_activation(f, act);
             }
             *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
             if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n_col) = acc[mt];
@@ -434,7 +435,7 @@ hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_
     hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks * plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq),
                        a.s_w, a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                       reinterpret_cast<half_t *>(a.out), a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan);
+                       reinterpret_cast<half_t *>(a.out), a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan, a.act);
     return hipGetLastError();
 }
 

@@ -72,7 +72,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBIT
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
-    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -332,11 +332,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
                 }
+                float f[4] = {(float)v[0] * (st * sc.x) + cb.x, (float)v[1] * (st * sc.y) + cb.y,
+                              (float)v[2] * (st * sc.z) + cb.z, (float)v[3] * (st * sc.w) + cb.w};
+                if (act != 0) {                   // wave-uniform
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) f[e] = apply_activation(f[e], act);
+                }
                 half4 o;
-                o[0] = (half_t)((float)v[0] * (st * sc.x) + cb.x);
-                o[1] = (half_t)((float)v[1] * (st * sc.y) + cb.y);
-                o[2] = (half_t)((float)v[2] * (st * sc.z) + cb.z);
-                o[3] = (half_t)((float)v[3] * (st * sc.w) + cb.w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
                 *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
                 if (acc_out != nullptr) {
                     const int m = mw + fm * 32 + lr;
@@ -377,7 +381,7 @@ hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS>), dim3(tiles_m * tiles_n),
                        dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq), a.s_w,
                        a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                       reinterpret_cast<half_t *>(a.out), a.acc_out, tiles_m, tiles_n);
+                       reinterpret_cast<half_t *>(a.out), a.acc_out, tiles_m, tiles_n, a.act);
     return hipGetLastError();
 }
 

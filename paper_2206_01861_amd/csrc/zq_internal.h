@@ -40,6 +40,7 @@ struct GemmArgs {
     void *workspace;
     size_t workspace_bytes;
     int w_bits;           // 8 or 4
+    int act;              // activation applied to acc*scale+bias before the FP16 rounding: 0 none, 1 GeLU erf, 2 GeLU tanh
 };
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);

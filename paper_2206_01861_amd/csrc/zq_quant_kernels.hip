@@ -42,32 +42,6 @@ __device__ __forceinline__ float row_max(float v, float *lds) {
     return v;
 }
 
-// GeLU, erf form: u * Phi(u) = max(u, 0) - |u| * h with h = erfc(|u| / sqrt2) / 2 from the rational
-// approximation of Abramowitz & Stegun 7.1.26 (absolute error of erf below 1.5e-7, i.e. below fp32
-// resolution of Phi); going through erfc keeps the relative accuracy of the negative tail.  The
-// constants carry the factors 1/sqrt2, 1/2 and log2(e).  About a third of the VALU work of the
-// library erff, which otherwise makes this memory-bound kernel compute-bound.
-__device__ __forceinline__ float gelu_erf(float u) {
-    const float a = fabsf(u);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, a, 1.0f));
-    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
-    p = fmaf(t, p, 0.5f * 1.421413741f);
-    p = fmaf(t, p, 0.5f * -0.284496736f);
-    p = fmaf(t, p, 0.5f * 0.254829592f);
-    const float w = u * 0.84932180028801904272f;      // sqrt(log2(e) / 2): exp(-u^2 / 2) = 2^(-w^2)
-    const float e = __builtin_amdgcn_exp2f(-(w * w));
-    const float h = (p * t) * e;
-    return fmaf(-a, h, __builtin_amdgcn_fmed3f(u, 0.0f, __builtin_inff()));   // max(u, 0) in one instruction
-}
-
-// GeLU, tanh form: 0.5 u (1 + tanh(v)) = u * (1 - 1 / (1 + exp(2v))).
-__device__ __forceinline__ float gelu_tanh(float u) {
-    const float c = 0.79788456080286535588f;
-    const float v = c * fmaf(0.044715f * u * u, u, u);
-    const float e = __builtin_amdgcn_exp2f(v * (2.0f * 1.44269504088896340736f));
-    return u * (1.0f - __builtin_amdgcn_rcpf(1.0f + e));
-}
-
 template <int OP, int TPR, int VPT>
 __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__ in, const half8 *__restrict__ p0,
                                                        const half8 *__restrict__ p1, float eps, int M, int K,

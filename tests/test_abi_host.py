@@ -133,6 +133,23 @@ def test_gemm_validation(fname, kmul):
     assert zq.force_gemm_variant(-1) == -1
 
 
+def test_gemm_gelu_quant_validation():
+    f = zq.lib().zq_gemm_gelu_quant_tokenwise
+
+    def call(xq=P, s_tok=P, wq=P, w_bits=8, s_w=P, groups=4, bias=None, tanh=0, M=8, N=64, K=128, g=P, gq=P, s=P):
+        return f(xq, s_tok, wq, w_bits, s_w, groups, bias, tanh, M, N, K, g, gq, s, None, 0, None)
+
+    assert call(w_bits=5) == E_UNSUP
+    assert call(tanh=2) == E_UNSUP
+    assert call(gq=None) == E_NULL
+    assert call(s=None) == E_NULL
+    assert call(g=None) == E_NULL                  # the activated FP16 tensor is the quantizer's input
+    assert call(wq=None) == E_NULL
+    assert call(N=32768 + 64, groups=4) == E_SHAPE # a row of g must fit the quantizer's registers
+    assert call(K=48, w_bits=4) == E_SHAPE
+    assert call(g=P + 8) == E_ALIGN
+
+
 def test_missing_library_is_an_error(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))

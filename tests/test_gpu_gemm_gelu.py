@@ -1,0 +1,83 @@
+"""GeMM with bias + GeLU in its epilogue, then token-wise quantization (the fusion of Sec. 4.3's
+bias-add + GeLU + quantization, moved into the dequantization epilogue of App. D), against the
+oracle: the FP16 activation within tolerance of the fp64 chain, the codes and scales bit-exact
+given that FP16 tensor."""
+import numpy as np
+import pytest
+import torch
+
+import zq_inputs
+from helpers import assert_bit_equal, dev, host
+from test_gpu_gemm import SIMPLE, SKINNY, SKINNY_SPLITK, TILE128, TILE256, TILE256X128, _case, orc, zq  # noqa: F401 (fixtures)
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_fused(orc, g16, gq, s, xq, s_tok, codes, s_w, bias, approx, what):
+    acc = orc.matmul_i32(xq, codes)
+    ref, mag = orc.dequant(acc, s_tok, s_w, bias)             # fp64 pre-activation and its term magnitudes
+    g_ref = orc.gelu_f64(ref, approx)
+    # fp32 evaluation of the pre-activation (a few ulp of its terms), |GeLU'| <= 1.13, the
+    # fp32 GeLU approximation (1.5e-7 absolute in Phi), then one FP16 rounding of the result.
+    tol = 2e-3 * np.abs(g_ref) + 4e-6 * (mag + 1.0) + 2.0 ** -24
+    err = np.abs(g16.astype(np.float64) - g_ref)
+    assert (err <= tol).all(), "%s: g off by %.3e (tol %.3e), %d bad" % (
+        what, err.max(), tol[np.unravel_index(err.argmax(), err.shape)], int((err > tol).sum()))
+    q_o, s_o = orc.quant_tokenwise(g16.astype(np.float32))
+    assert_bit_equal(s, s_o, what + " s_tok")
+    assert_bit_equal(gq, q_o, what + " codes")
+
+
+CASES = [
+    (SIMPLE, 17, 768, 784, 48), (TILE128, 300, 400, 384, 25), (TILE128, 515, 1024, 1024, 64),
+    (TILE256, 300, 528, 512, 33), (TILE256X128, 300, 400, 512, 25), (SKINNY, 8, 6144, 2048, 128),
+    (SKINNY, 100, 768, 768, 48), (SKINNY_SPLITK, 33, 2064, 8192, 3), (-1, 128, 4096, 1024, 64),
+    (-1, 16, 4096, 1024, 64),
+]
+
+
+@pytest.mark.parametrize("approx", [False, True])
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("variant,M,N,K,g", CASES)
+def test_gemm_gelu_quant_against_oracle(zq, orc, variant, M, N, K, g, bits, approx):
+    print("gemm+gelu", variant, bits, M, N, K, g, approx, flush=True)
+    if bits == 4 and K % 32:
+        pytest.skip("INT4 needs K % 32 == 0")
+    rng = zq_inputs.rng_for(6, variant * 1000 + M + N + K + bits)
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
+    # scales that put the pre-activation where GeLU bends: |u| of a few units
+    s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
+    nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+    if variant == SKINNY_SPLITK and nbytes == 0:
+        pytest.skip("shape does not split")
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda") if variant in (SKINNY_SPLITK, -1) else None
+    prev = zq.force_gemm_variant(variant)
+    try:
+        g16, gq, s = zq.zq_gemm_gelu_quant_tokenwise(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias),
+                                                     approx_tanh=approx, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        zq.force_gemm_variant(prev)
+    _check_fused(orc, host(g16), host(gq), host(s), xq, s_tok, codes, s_w, bias, approx,
+                 "fused %s %d-bit %dx%dx%d" % (zq.gemm_variant_name(variant), bits, M, N, K))
+
+
+def test_fused_chain_tracks_two_call_chain(zq, orc):
+    """The fused call and GeMM -> GeLU+quant differ only by the FP16 rounding of the pre-activation:
+    codes agree except where that rounding moves a value across a quantization boundary."""
+    rng = zq_inputs.rng_for(2, 9)
+    M, H, F, g = 256, 1024, 4096, 64
+    x = zq_inputs.config_activations("c2", rng, M, H)
+    gamma, beta = zq_inputs.layernorm_params(rng, H)
+    w1, b1 = zq_inputs.weights(rng, F, H), zq_inputs.bias(rng, F)
+    wq1, sw1 = zq.zq_quantize_weight_groupwise(dev(w1), g, 8)
+    xq, st, _ = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), dev(beta), 1e-5)
+    h, _, _, _ = zq.zq_gemm_i8_dequant(xq, st, wq1, sw1, dev(b1))
+    hq, st2, _ = zq.zq_gelu_quant_tokenwise(h, None)
+    g16, gq, s = zq.zq_gemm_gelu_quant_tokenwise(xq, st, wq1, sw1, dev(b1))
+    torch.cuda.synchronize()
+    _check_fused(orc, host(g16), host(gq), host(s), host(xq), host(st), host(wq1), host(sw1), b1, False, "chain")
+    rel_s = np.abs(host(s) - host(st2)) / host(st2)
+    assert rel_s.max() < 2e-3
+    diff = np.abs(host(gq).astype(np.int32) - host(hq).astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).mean() < 0.05
