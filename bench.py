@@ -105,6 +105,8 @@ class FFCPair:
         self.hq = torch.empty((tokens, ffn), dtype=torch.int8, device=d)
         self.st2 = torch.empty(tokens, dtype=torch.float32, device=d)
         self.o = torch.empty((tokens, hidden), dtype=torch.float16, device=d)
+        self.acc1 = torch.empty((tokens, ffn), dtype=torch.int32, device=d)      # only the unfused ablation uses these
+        self.acc2 = torch.empty((tokens, hidden), dtype=torch.int32, device=d)
         self.ops = 2.0 * tokens * (hidden * ffn + ffn * hidden)
         self.gemm_ops = 2.0 * tokens * hidden * ffn          # per GeMM launch (both are equal)
 
@@ -135,6 +137,21 @@ class FFCPair:
         self.ln()
         self.gemm1_gelu()
         self.gemm2()
+
+    def unfused_step(self, _=0):
+        """The pipeline the fusions replace (Fig. 2, left): FP16 LayerNorm and GeLU as kernels of their own
+        (torch), a separate quantization kernel, a GeMM that writes its INT32 accumulators to memory and a
+        separate dequantization kernel.  (The GeMM call also writes its FP16 output, which this chain ignores.)"""
+        F = torch.nn.functional
+        zq = self.zq
+        y = F.layer_norm(self.x, (self.H,), self.gamma, self.beta, 1e-5)
+        zq.zq_quantize_tokenwise(y, out=(self.xq, self.st))
+        zq.zq_gemm_i8_dequant(self.xq, self.st, self.wq1, self.sw1, None, out=self.h, acc_out=self.acc1)
+        zq.zq_dequantize_acc(self.acc1, self.st, self.sw1, self.b1, out=self.h)
+        a = F.gelu(self.h)
+        zq.zq_quantize_tokenwise(a, out=(self.hq, self.st2))
+        zq.zq_gemm_i8_dequant(self.hq, self.st2, self.wq2, self.sw2, None, out=self.o, acc_out=self.acc2)
+        zq.zq_dequantize_acc(self.acc2, self.st2, self.sw2, self.b2, out=self.o)
 
     def fp16_step(self, _=0):
         F = torch.nn.functional
@@ -200,6 +217,13 @@ def run_default(args):
                  "gemm_ffc1_gelu_quant_us": time_graph(graph_of(wl.gemm1_gelu, 20), 10, 20) * 1e3,
                  "note": "zq_gemm_gelu_quant_tokenwise replaces GeMM 1 + GeLU+quant; not the headline value"}
 
+    unfused = None
+    if not args.no_fused:
+        unfused_ms = time_graph(graph_of(wl.unfused_step, spg), replays, spg)
+        unfused = {"ms_per_step": unfused_ms, "fusion_speedup": unfused_ms / ms_per_step,
+                   "note": "Fig. 2 (left): separate LayerNorm / GeLU (torch FP16), quantization, INT32 GeMM output and "
+                           "dequantization kernels; eight launches instead of four"}
+
     gf = graph_of(wl.fp16_step, spg)
     fp16_ms = time_graph(gf, replays, spg)
     fp16_gemm_us = time_graph(graph_of(lambda i: torch.nn.functional.linear(wl.x, wl.w1, wl.b1), 20), 10, 20) * 1e3
@@ -224,6 +248,7 @@ def run_default(args):
             "gelu_quant_GBs": (3.0 * wl.M * wl.F + 4 * wl.M) / (calls["gelu_quant"] * 1e-6) / 1e9,
             "peak_GBs": PEAK_HBM_GBS},
         "fused_gelu_epilogue": fused,
+        "unfused_pipeline": unfused,
         "fp16": {"ms_per_step": fp16_ms, "speedup_chain": fp16_ms / ms_per_step,
                  "gemm_ffc1_us": fp16_gemm_us, "speedup_gemm_ffc1": fp16_gemm_us / calls["gemm_ffc1"]},
         "paper_context": "ZeroQuant reports whole-model W8A8 speed-ups on A100-40GB only "

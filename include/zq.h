@@ -138,6 +138,30 @@ zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8
                                void *workspace, size_t workspace_bytes, zq_stream stream);
 
 /*
+ * The two operators of the unfused pipeline (Fig. 2, left; Sec. 4.3 calls the
+ * stand-alone quantizer "an efficient parallel implementation of the
+ * quantization operator"), kept as calls of their own: for layers whose
+ * producer is not LayerNorm or GeLU, and to measure what the fusions save.
+ *
+ * zq_quantize_tokenwise: token-wise INT8 quantization (App. A.2, one scale per
+ * row) of an FP16 tensor.
+ *   x_fp16   in,  fp16 [M,K] row-major (device)
+ *   xq_out   out, int8 [M,K];  s_tok_out  out, fp32 [M]  (device)
+ * K % 16 == 0, K <= 32768.  Errors as zq_layernorm_quant_tokenwise.
+ *
+ * zq_dequantize_acc: out[m,n] = fp16( acc[m,n] * s_tok[m] * s_w[n / (N/groups)] + bias[n] ),
+ * the dequantization epilogue of App. D as a kernel of its own (fp32
+ * arithmetic, one FP16 rounding; agrees with the GeMM calls' output for the
+ * same acc to within one FP16 step).
+ *   acc      in,  int32 [M,N] (device);  s_tok fp32 [M];  s_w fp32 [groups];  bias_fp16 fp16 [N] or NULL
+ *   out_fp16 out, fp16 [M,N] (device)
+ * N % groups == 0, (N/groups) % 16 == 0.  ZQ_ERR_NULL / ZQ_ERR_SHAPE / ZQ_ERR_ALIGN as elsewhere.
+ */
+zq_status zq_quantize_tokenwise(const void *x_fp16, int M, int K, int8_t *xq_out, float *s_tok_out, zq_stream stream);
+zq_status zq_dequantize_acc(const int32_t *acc, const float *s_tok, const float *s_w, int groups,
+                            const void *bias_fp16, int M, int N, void *out_fp16, zq_stream stream);
+
+/*
  * First feed-forward GeMM with the activation in its epilogue (Sec. 4.3 and
  * App. D fuse bias-add + GeLU with the token-wise quantization that feeds the
  * second GeMM; here the bias-add and the GeLU move one step earlier, into the

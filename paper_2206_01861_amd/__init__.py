@@ -14,10 +14,12 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     version,
+    zq_dequantize_acc,
     zq_gelu_quant_tokenwise,
     zq_gemm_gelu_quant_tokenwise,
     zq_gemm_i8_dequant,
     zq_gemm_w4a8_dequant,
     zq_layernorm_quant_tokenwise,
+    zq_quantize_tokenwise,
     zq_quantize_weight_groupwise,
 )

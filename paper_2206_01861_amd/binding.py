@@ -16,7 +16,7 @@ _lib = None
 SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
-    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise",
+    "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise", "zq_quantize_tokenwise", "zq_dequantize_acc",
 ]
 
 
@@ -59,6 +59,10 @@ def lib():
     L.zq_gemm_w4a8_dequant.argtypes = gemm_args
     L.zq_gemm_gelu_quant_tokenwise.restype = ci
     L.zq_gemm_gelu_quant_tokenwise.argtypes = [vp, vp, vp, ci, vp, ci, vp, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    L.zq_quantize_tokenwise.restype = ci
+    L.zq_quantize_tokenwise.argtypes = [vp, ci, ci, vp, vp, vp]
+    L.zq_dequantize_acc.restype = ci
+    L.zq_dequantize_acc.argtypes = [vp, vp, vp, ci, vp, ci, ci, vp, vp]
     L.zq_debug_force_gemm_variant.restype = ci
     L.zq_debug_force_gemm_variant.argtypes = [ci]
     L.zq_gemm_variant_name.restype = ctypes.c_char_p
@@ -174,7 +178,7 @@ def zq_gelu_quant_tokenwise(h_fp16, bias_fp16=None, approx_tanh=False, y_dtype=N
     return xq, s_tok, y
 
 
-def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspace, out):
+def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspace, out, acc_out=None):
     _dev(xq, torch.int8, "xq")
     _dev(s_tok, torch.float32, "s_tok")
     _dev(wq, wdtype, "wq")
@@ -186,7 +190,9 @@ def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspac
     dev = xq.device
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=dev)
-    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    acc = acc_out if acc_out is not None else (torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None)
+    if acc is not None:
+        _dev(acc, torch.int32, "acc_out")
     out_q = torch.empty((M, N), dtype=torch.int8, device=dev) if requant else None
     out_s = torch.empty(M, dtype=torch.float32, device=dev) if requant else None
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -196,19 +202,19 @@ def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspac
 
 
 def zq_gemm_i8_dequant(xq, s_tok, wq, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,
-                       out=None):
+                       out=None, acc_out=None):
     """-> (out fp16 [M,N], acc int32 | None, out_q int8 | None, out_s_tok fp32 | None)."""
     return _gemm(lib().zq_gemm_i8_dequant, torch.int8, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant,
-                 workspace, out)
+                 workspace, out, acc_out)
 
 
 def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,
-                         out=None):
+                         out=None, acc_out=None):
     """INT4-packed weights uint8 [N,K/2]; otherwise as zq_gemm_i8_dequant."""
     if wq4.shape[1] * 2 != xq.shape[1]:
         raise ValueError("wq4 must be [N, K/2]")
     return _gemm(lib().zq_gemm_w4a8_dequant, torch.uint8, xq, s_tok, wq4, s_w, bias_fp16, want_acc, requant,
-                 workspace, out)
+                 workspace, out, acc_out)
 
 
 def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh=False, workspace=None, out=None):
@@ -243,3 +249,29 @@ def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh
                                               _ptr(bias_fp16), 1 if approx_tanh else 0, M, N, K, _ptr(g), _ptr(gq),
                                               _ptr(s), _ptr(workspace), ws_bytes, _stream()))
     return g, gq, s
+
+
+def zq_quantize_tokenwise(x_fp16, out=None):
+    """x fp16 [M,K] -> (xq int8 [M,K], s_tok fp32 [M])."""
+    _dev(x_fp16, torch.float16, "x_fp16")
+    M, K = x_fp16.shape
+    xq, s_tok = out if out is not None else (
+        torch.empty((M, K), dtype=torch.int8, device=x_fp16.device),
+        torch.empty(M, dtype=torch.float32, device=x_fp16.device))
+    _check(lib().zq_quantize_tokenwise(_ptr(x_fp16), M, K, _ptr(xq), _ptr(s_tok), _stream()))
+    return xq, s_tok
+
+
+def zq_dequantize_acc(acc, s_tok, s_w, bias_fp16=None, out=None):
+    """acc int32 [M,N] -> fp16 [M,N] = acc * s_tok[row] * s_w[group] + bias."""
+    _dev(acc, torch.int32, "acc")
+    _dev(s_tok, torch.float32, "s_tok")
+    _dev(s_w, torch.float32, "s_w")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, N = acc.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=acc.device)
+    _check(lib().zq_dequantize_acc(_ptr(acc), _ptr(s_tok), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N,
+                                   _ptr(out), _stream()))
+    return out

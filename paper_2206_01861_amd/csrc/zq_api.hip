@@ -115,6 +115,26 @@ zq_status zq_gelu_quant_tokenwise(const void *h_fp16, const void *bias_fp16, int
     return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
 }
 
+zq_status zq_quantize_tokenwise(const void *x_fp16, int M, int K, int8_t *xq_out, float *s_tok_out, zq_stream stream) {
+    zq_status s = check_rowquant(x_fp16, nullptr, nullptr, M, K, xq_out, s_tok_out, nullptr, 0);
+    if (s != ZQ_OK) return s;
+    hipError_t e = zq::launch_rowquant(zq::kOpIdentity, x_fp16, nullptr, nullptr, 0.0f, M, K, xq_out, s_tok_out,
+                                       nullptr, 0, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
+zq_status zq_dequantize_acc(const int32_t *acc, const float *s_tok, const float *s_w, int groups,
+                            const void *bias_fp16, int M, int N, void *out_fp16, zq_stream stream) {
+    if (acc == nullptr || s_tok == nullptr || s_w == nullptr || out_fp16 == nullptr) return ZQ_ERR_NULL;
+    if (M <= 0 || N <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
+    if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
+    if (misaligned(acc) || misaligned(s_tok) || misaligned(s_w) || misaligned(bias_fp16) || misaligned(out_fp16))
+        return ZQ_ERR_ALIGN;
+    hipError_t e = zq::launch_dequant(acc, s_tok, s_w, groups, bias_fp16, M, N, out_fp16,
+                                      reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
 size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits) {
     if (M <= 0 || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return 0;
     size_t best = 0;

@@ -13,6 +13,10 @@ enum RowOp { kOpLayerNorm = 0, kOpGeluErf = 1, kOpGeluTanh = 2, kOpIdentity = 3 
 hipError_t launch_rowquant(RowOp op, const void *in, const void *p0, const void *p1, float eps, int M, int K,
                            int8_t *xq, float *s_tok, void *y_out, int y_dtype, hipStream_t st);
 
+// out fp16 [M,N] = acc * s_tok[row] * s_w[col group] + bias, the GeMM epilogue as a kernel of its own.
+hipError_t launch_dequant(const int32_t *acc, const float *s_tok, const float *s_w, int groups, const void *bias, int M,
+                          int N, void *out, hipStream_t st);
+
 hipError_t launch_weight_quant(const void *w, int N, int K, int groups, int bits, void *wq, float *s_w,
                                hipStream_t st);
 

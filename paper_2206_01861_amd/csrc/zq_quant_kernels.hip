@@ -200,6 +200,45 @@ hipError_t launch_rowquant(RowOp op, const void *in, const void *p0, const void 
 }
 
 // ---------------------------------------------------------------------------
+// Stand-alone dequantization of an INT32 accumulator tensor: the separate
+// kernel of the unfused pipeline (Fig. 2, left) that the GeMM epilogue
+// replaces (fp32 arithmetic, one FP16 rounding).
+// One thread per four consecutive columns (a group holds a multiple of 16).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequant_kernel(const int32x4 *__restrict__ acc, const float *__restrict__ s_tok,
+                                                      const float *__restrict__ s_w, int gs,
+                                                      const half_t *__restrict__ bias, int M, int N,
+                                                      half4 *__restrict__ out) {
+    const int nq = N >> 2;
+    const long total = (long)M * nq;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int m = (int)(i / nq);
+        const int n = (int)(i - (long)m * nq) * 4;
+        const int32x4 v = acc[i];
+        const float sc = s_tok[m] * s_w[n / gs];
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float f = (float)v[e] * sc;
+            if (bias != nullptr) f += (float)bias[n + e];
+            o[e] = (half_t)f;
+        }
+        out[i] = o;
+    }
+}
+
+hipError_t launch_dequant(const int32_t *acc, const float *s_tok, const float *s_w, int groups, const void *bias, int M,
+                          int N, void *out, hipStream_t st) {
+    const long total = (long)M * (N / 4);
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const int32x4 *>(acc),
+                       s_tok, s_w, N / groups, reinterpret_cast<const half_t *>(bias), M, N,
+                       reinterpret_cast<half4 *>(out));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Group-wise weight quantization.  A group is a contiguous chunk of gs*K fp16
 // values.  Four launches: clear, absmax (integer atomic max on the fp32 bit
 // pattern, exact and order independent), quantize, and turn absmax into the

@@ -150,6 +150,23 @@ def test_gemm_gelu_quant_validation():
     assert call(g=P + 8) == E_ALIGN
 
 
+def test_standalone_quantizer_and_dequantizer_validation():
+    q = zq.lib().zq_quantize_tokenwise
+    assert q(None, 4, 64, P, P, None) == E_NULL
+    assert q(P, 4, 64, None, P, None) == E_NULL
+    assert q(P, 0, 64, P, P, None) == E_SHAPE
+    assert q(P, 4, 72, P, P, None) == E_SHAPE
+    assert q(P, 4, 32768 + 16, P, P, None) == E_SHAPE
+    assert q(P + 4, 4, 64, P, P, None) == E_ALIGN
+    d = zq.lib().zq_dequantize_acc
+    assert d(None, P, P, 4, None, 8, 64, P, None) == E_NULL
+    assert d(P, P, P, 4, None, 8, 64, None, None) == E_NULL
+    assert d(P, P, P, 3, None, 8, 64, P, None) == E_SHAPE
+    assert d(P, P, P, 8, None, 8, 64, P, None) == E_SHAPE          # 8 columns per group
+    assert d(P, P, P, 4, None, 0, 64, P, None) == E_SHAPE
+    assert d(P, P, P, 4, P + 2, 8, 64, P, None) == E_ALIGN
+
+
 def test_missing_library_is_an_error(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))

@@ -120,6 +120,29 @@ def test_no_bias_and_extreme_codes(zq, orc):
         _check(orc, res, xq, s_tok, wq, s_w, None, "extreme")
 
 
+def test_largest_k_fills_the_accumulator(zq, orc):
+    """K at the largest accepted values with every product at +-127*127: the INT32 accumulator ends
+    within 0.01 % of its range and must not wrap in any schedule."""
+    M, N, g = 3, 32, 2
+    for K, variants in ((133136, (SIMPLE,)),                                  # largest K the ABI takes (K % 16 == 0)
+                        (133120, (SIMPLE, TILE128, TILE256, TILE256X128, SKINNY, SKINNY_SPLITK))):
+        xq = np.full((M, K), 127, np.int8)
+        xq[1] = -127
+        wq = np.full((N, K), 127, np.int8)
+        wq[1::2] = -127
+        s_tok = np.full(M, 1e-4, np.float32)
+        s_w = np.full(g, 1e-5, np.float32)
+        want = np.outer(np.array([1, -1, 1], np.int64), np.where(np.arange(N) % 2 == 0, 1, -1)) * (16129 * K)
+        assert np.abs(want).max() < 2 ** 31
+        for variant in variants:
+            nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
+            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+            res = _run(zq, 8, variant, xq, s_tok, wq, s_w, None, workspace=ws)
+            assert np.array_equal(host(res[1]).astype(np.int64), want), (K, variant)
+            ref, mag = orc.dequant(want.astype(np.int32), s_tok, s_w, None)
+            assert_out_close(host(res[0]), ref, mag, "largest K %d variant %d" % (K, variant))
+
+
 def test_requant_epilogue(zq, orc):
     rng = zq_inputs.rng_for(4, 77)
     M, N, K, g = 37, 256, 512, 16

@@ -123,3 +123,45 @@ def test_gelu_quant(zq, orc, approx, M, N):
     xq_nb, s_nb, y_nb = zq.zq_gelu_quant_tokenwise(dev(h), None, approx_tanh=approx, y_dtype=torch.float32)
     y64_nb, _ = orc.gelu(h, None, approx_tanh=approx)
     check_fused_codes(host(xq_nb), host(s_nb), host(y_nb), y64_nb, "gelu no bias")
+
+
+@pytest.mark.parametrize("M,K", [(1, 16), (5, 768), (64, 4096), (3, 32768), (130, 1040)])
+def test_standalone_tokenwise_quantizer(zq, orc, M, K):
+    """The quantization operator on its own (Sec. 4.3): bit-exact against the oracle, zero rows included."""
+    rng = zq_inputs.rng_for(3, 900 + M + K)
+    x = zq_inputs.activations(rng, M, K, outlier_frac=0.01, outlier_scale=15.0)
+    if M > 2:
+        x[2] = 0
+    xq, s = zq.zq_quantize_tokenwise(dev(x))
+    torch.cuda.synchronize()
+    q_o, s_o = orc.quant_tokenwise(x.astype(np.float32))
+    assert_bit_equal(host(s), s_o, "s_tok")
+    assert_bit_equal(host(xq), q_o, "xq")
+
+
+@pytest.mark.parametrize("M,N,g", [(1, 16, 1), (37, 256, 16), (300, 4096, 64), (5, 48, 3)])
+def test_standalone_dequantizer(zq, orc, M, N, g):
+    """The dequantization epilogue as its own kernel (App. D): within the FP16 tolerance of the fp64
+    reference, and within one FP16 step of what the GeMM writes for the same accumulators (a fused
+    multiply-add in one epilogue and a separate multiply and add in another may round differently)."""
+    from helpers import assert_out_close
+    rng = zq_inputs.rng_for(3, 950 + M + N)
+    acc = rng.integers(-2 ** 30, 2 ** 30, size=(M, N), dtype=np.int64).astype(np.int32)
+    acc[0, :4] = [0, 1, -1, 2 ** 31 - 1]
+    s_tok = zq_inputs.random_scales(rng, M, 1e-7, 1e-5)
+    s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-2)
+    bias = zq_inputs.bias(rng, N)
+    for b in (bias, None):
+        out = zq.zq_dequantize_acc(dev(acc), dev(s_tok), dev(s_w), None if b is None else dev(b))
+        torch.cuda.synchronize()
+        ref, mag = orc.dequant(acc, s_tok, s_w, b)
+        assert_out_close(host(out), ref, mag, "dequant %dx%d" % (M, N))
+    # agrees with the fused epilogue
+    K = 256
+    xq = zq_inputs.random_codes(rng, (M, K))
+    wq = zq_inputs.random_codes(rng, (N, K))
+    o, a, _, _ = zq.zq_gemm_i8_dequant(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias), want_acc=True)
+    o2 = zq.zq_dequantize_acc(a, dev(s_tok), dev(s_w), dev(bias))
+    torch.cuda.synchronize()
+    d = (o.float() - o2.float()).abs()
+    assert bool((d <= o.float().abs() * 2.0 ** -10 + 2.0 ** -24).all())
