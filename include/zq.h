@@ -199,6 +199,25 @@ const char *zq_gemm_variant_name(int variant);
 int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes);
 
 /*
+ * Measured schedule table (App. D ranks schedules by measuring them offline
+ * and picks by batch x sequence length at run time).  zq_tune_set registers,
+ * for the GeMM shape (N, K, w_bits) and token counts m_lo..m_hi, the schedule
+ * `variant` to use instead of the built-in choice and, for the two streaming
+ * schedules, the cut (row_blocks, k_splits; both 0 = keep the cost model's).
+ * An entry is ignored for a call whose workspace cannot hold its K split.
+ * The latest matching entry wins.  zq_gemm_workspace_bytes, zq_gemm_choose_variant
+ * and zq_gemm_stream_plan reflect the table.  Process-wide; not for use
+ * concurrently with GeMM calls.  The Python module paper_2206_01861_amd.autotune
+ * fills the table by timing the candidates on the installed GPU.
+ * Returns ZQ_OK, ZQ_ERR_SHAPE (ranges, or a cut the kernels cannot run:
+ * more than eight strips per row block, more splits than stages, ...),
+ * ZQ_ERR_UNSUPPORTED (unknown variant, a cut for a non-streaming schedule).
+ */
+int zq_tune_set(int m_lo, int m_hi, int N, int K, int w_bits, int variant, int row_blocks, int k_splits);
+void zq_tune_clear(void);
+int zq_tune_count(void);
+
+/*
  * How the weight-streaming schedules (M <= 128, K a multiple of 256) cut a
  * GeMM over the chip (Sec. 4.3: small-batch latency is weight-loading time,
  * so the cut is made for memory bandwidth): the N/16 strips of 16 weight rows

@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     gemm_workspace_bytes,
     force_gemm_variant,
     lib,
+    tune_clear,
+    tune_count,
+    tune_set,
     lib_path,
     version,
     zq_dequantize_acc,

@@ -17,6 +17,7 @@ SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
     "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise", "zq_quantize_tokenwise", "zq_dequantize_acc",
+    "zq_tune_set", "zq_tune_clear", "zq_tune_count",
 ]
 
 
@@ -63,6 +64,12 @@ def lib():
     L.zq_quantize_tokenwise.argtypes = [vp, ci, ci, vp, vp, vp]
     L.zq_dequantize_acc.restype = ci
     L.zq_dequantize_acc.argtypes = [vp, vp, vp, ci, vp, ci, ci, vp, vp]
+    L.zq_tune_set.restype = ci
+    L.zq_tune_set.argtypes = [ci] * 8
+    L.zq_tune_clear.restype = None
+    L.zq_tune_clear.argtypes = []
+    L.zq_tune_count.restype = ci
+    L.zq_tune_count.argtypes = []
     L.zq_debug_force_gemm_variant.restype = ci
     L.zq_debug_force_gemm_variant.argtypes = [ci]
     L.zq_gemm_variant_name.restype = ctypes.c_char_p
@@ -114,6 +121,19 @@ def gemm_variant_name(variant):
 
 def gemm_choose_variant(M, N, K, w_bits=8, workspace_bytes=0):
     return lib().zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes)
+
+
+def tune_set(m_lo, m_hi, N, K, w_bits, variant, row_blocks=0, k_splits=0):
+    """Register a measured schedule (and streaming cut) for a shape; see zq_tune_set in include/zq.h."""
+    _check(lib().zq_tune_set(m_lo, m_hi, N, K, w_bits, variant, row_blocks, k_splits))
+
+
+def tune_clear():
+    lib().zq_tune_clear()
+
+
+def tune_count():
+    return lib().zq_tune_count()
 
 
 def gemm_stream_plan(M, N, K, w_bits=8, workspace_bytes=0):

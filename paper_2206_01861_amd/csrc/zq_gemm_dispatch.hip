@@ -4,6 +4,9 @@
 #include "../../include/zq.h"
 #include "zq_internal.h"
 
+#include <mutex>
+#include <vector>
+
 namespace zq {
 
 constexpr int kStreamMaxTokens = 128;   // the weight-streaming schedules hold up to eight 16-token tiles
@@ -13,6 +16,36 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st);
 hipError_t launch_gemm_skinny(const GemmArgs &a, bool split_k, hipStream_t st);
 size_t stream_workspace_bytes(int M, int N, int K, int w_bits);
 void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers);
+
+// Measured overrides of the built-in choices (the profiler-driven schedule search of App. D, kept
+// as a table the caller fills): exact (N, K, bits), a range of M.
+namespace {
+struct TuneEntry {
+    int m_lo, m_hi, N, K, w_bits, variant, row_blocks, k_splits;
+};
+std::mutex g_tune_mutex;
+std::vector<TuneEntry> g_tune;
+
+bool tune_lookup(int M, int N, int K, int w_bits, TuneEntry *out) {
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    for (auto it = g_tune.rbegin(); it != g_tune.rend(); ++it) {     // the latest entry wins
+        if (it->N == N && it->K == K && it->w_bits == w_bits && M >= it->m_lo && M <= it->m_hi) {
+            *out = *it;
+            return true;
+        }
+    }
+    return false;
+}
+}  // namespace
+
+bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_splits) {
+    TuneEntry e;
+    if (!tune_lookup(M, N, K, w_bits, &e) || e.row_blocks <= 0) return false;
+    if (e.variant != kGemmSkinny && e.variant != kGemmSkinnySplitK) return false;
+    *row_blocks = e.row_blocks;
+    *k_splits = e.k_splits;
+    return true;
+}
 
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits) {
     if (variant != kGemmSkinnySplitK || M > kStreamMaxTokens || (K % 256) != 0) return 0;
@@ -52,6 +85,10 @@ hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st) {
 
 extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t workspace_bytes) {
     using namespace zq;
+    TuneEntry tuned;
+    if (tune_lookup(M, N, K, w_bits, &tuned) &&
+        gemm_variant_supports(tuned.variant, M, N, K, w_bits, workspace_bytes))
+        return tuned.variant;
     // Up to 64 tokens every shape is bound by the weight stream; up to 128 tokens the streaming
     // schedules still win once K is long enough that the activation tile is a small part of the traffic.
     if (M <= 64 || (M <= kStreamMaxTokens && K >= 2048 && (K % 256) == 0)) {
@@ -62,6 +99,9 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
         if (M <= 64) return kGemmSimple;
     }
     if ((K % 128) != 0) return kGemmSimple;
+    // Tiny problems (a BERT-base layer at 128 tokens) are all latency: one wave per 16x16 tile straight
+    // from global memory starts and finishes sooner than a handful of LDS-tiled workgroups (6.2 vs 6.8 us).
+    if ((long)M * N * K <= (1L << 27)) return kGemmSimple;
     // 256x256 tiles once they fill the chip; 128x128 tiles waste less on ragged or small problems.
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
     if (t256 >= 160) return kGemmTile256;
@@ -77,4 +117,32 @@ extern "C" int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t works
     const bool split = workspace_bytes > 0 && workspace_bytes >= stream_workspace_bytes(M, N, K, w_bits);
     stream_plan(M, N, K, w_bits, split, row_blocks, k_splits, consumers);
     return ZQ_OK;
+}
+
+extern "C" int zq_tune_set(int m_lo, int m_hi, int N, int K, int w_bits, int variant, int row_blocks, int k_splits) {
+    using namespace zq;
+    if (m_lo <= 0 || m_hi < m_lo || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return ZQ_ERR_SHAPE;
+    if (variant < 0 || variant >= kGemmVariantCount) return ZQ_ERR_UNSUPPORTED;
+    const bool streaming = variant == kGemmSkinny || variant == kGemmSkinnySplitK;
+    if (row_blocks != 0 || k_splits != 0) {
+        if (!streaming || (N % 16) != 0 || (K % 256) != 0 || m_hi > kStreamMaxTokens) return ZQ_ERR_UNSUPPORTED;
+        const int strips = N / 16, stages = K / 256;
+        if (row_blocks < 1 || row_blocks > strips || (strips + row_blocks - 1) / row_blocks > 8) return ZQ_ERR_SHAPE;
+        if (k_splits < 1 || k_splits > stages) return ZQ_ERR_SHAPE;
+        if ((variant == kGemmSkinny) != (k_splits == 1)) return ZQ_ERR_SHAPE;   // a K split is the split schedule
+        if (k_splits > 1 && (strips > 8192 || (double)k_splits * m_hi * N * 4.0 >= 2147483648.0)) return ZQ_ERR_SHAPE;
+    }
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    g_tune.push_back(TuneEntry{m_lo, m_hi, N, K, w_bits, variant, row_blocks, k_splits});
+    return ZQ_OK;
+}
+
+extern "C" void zq_tune_clear(void) {
+    std::lock_guard<std::mutex> lock(zq::g_tune_mutex);
+    zq::g_tune.clear();
+}
+
+extern "C" int zq_tune_count(void) {
+    std::lock_guard<std::mutex> lock(zq::g_tune_mutex);
+    return (int)zq::g_tune.size();
 }

@@ -414,6 +414,9 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     }
     for (int m = 1; m <= 8; ++m)
         for (int ksp = 1; ksp <= 4; ++ksp) consider(kCUs * m / ksp, ksp);   // whole multiples of the CU count
+    int trb = 0, tks = 0;
+    if (tuned_stream_plan(M, N, K, w_bits, &trb, &tks) && (tks == 1 || allow_split))   // validated when registered
+        best = StreamPlan{S, St, trb, tks, (S + trb - 1) / trb};
     if (best.row_blocks == 0) {                       // cannot happen (c = 1, no split is always admissible)
         best = StreamPlan{S, St, S, 1, 1};
     }

@@ -47,6 +47,9 @@ struct GemmArgs {
     int act;              // activation applied to acc*scale+bias before the FP16 rounding: 0 none, 1 GeLU erf, 2 GeLU tanh
 };
 
+// A caller-supplied cut of the streaming schedules for this shape, if one was registered.
+bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_splits);
+
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);
 hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st);

@@ -167,6 +167,40 @@ def test_standalone_quantizer_and_dequantizer_validation():
     assert d(P, P, P, 4, P + 2, 8, 64, P, None) == E_ALIGN
 
 
+def test_tuning_table_overrides_the_choice():
+    zq.tune_clear()
+    try:
+        M, N, K = 16, 4096, 4096
+        base = zq.gemm_choose_variant(M, N, K, 8, 0)
+        assert zq.gemm_variant_name(base) == "skinny"
+        zq.tune_set(1, 32, N, K, 8, 1)                              # 128x128 tiles for 1..32 tokens
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, 0)) == "tile128"
+        assert zq.gemm_choose_variant(33, N, K, 8, 0) == zq.gemm_choose_variant(33, N, K, 4, 0)   # outside the range
+        assert zq.gemm_choose_variant(M, N, K, 4, 0) == base        # other bit width untouched
+        # a streaming cut with a K split: the workspace query and the plan follow it
+        zq.tune_set(1, 32, N, K, 8, 4, 64, 4)
+        ws = zq.gemm_workspace_bytes(M, N, K, 8)
+        assert ws == 4 * M * N * 4
+        assert zq.gemm_stream_plan(M, N, K, 8, ws) == (64, 4, 4)
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws)) == "skinny_splitk"
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, 0)) == "skinny"   # no workspace: entry ignored
+        assert zq.gemm_stream_plan(M, N, K, 8, 0)[1] == 1
+        assert zq.tune_count() == 2
+        for bad in ((1, 32, N, K, 8, 3, 16, 1),      # 16 strips per row block: more than a workgroup has waves
+                    (1, 32, N, K, 8, 3, 64, 4),      # a K split belongs to the split schedule
+                    (1, 32, N, K, 8, 4, 64, 17),     # more splits than stages
+                    (32, 1, N, K, 8, 1, 0, 0), (1, 32, N, K, 5, 1, 0, 0)):
+            with pytest.raises(zq.ZQError):
+                zq.tune_set(*bad)
+        with pytest.raises(zq.ZQError):
+            zq.tune_set(1, 32, N, K, 8, 9)
+        with pytest.raises(zq.ZQError):
+            zq.tune_set(1, 32, N, K, 8, 1, 64, 1)    # a cut for a tiled schedule
+    finally:
+        zq.tune_clear()
+    assert zq.tune_count() == 0 and zq.gemm_choose_variant(16, 4096, 4096, 8, 0) == base
+
+
 def test_missing_library_is_an_error(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))

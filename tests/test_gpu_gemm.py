@@ -253,3 +253,25 @@ def test_full_size_workloads(zq, orc, name, M):
         err = (out[m0:m0 + step].to(torch.float64) - (p + b64[None, :])).abs()
         tol = 2e-3 * (p.abs() + b64.abs()[None, :]) + 2.0 ** -25
         assert bool((err <= tol).all()), name + " epilogue"
+
+
+def test_autotune_registers_a_runnable_schedule(zq, orc):
+    """The measured schedule table (App. D's offline ranking): whatever the tuner picks for a shape
+    must reproduce the oracle's accumulators, and clearing the table restores the built-in choice."""
+    from paper_2206_01861_amd import autotune
+    rng = zq_inputs.rng_for(4, 79)
+    for (M, N, K, g, bits) in [(16, 2048, 2048, 128, 8), (8, 1024, 4096, 64, 4)]:
+        xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
+        base = zq.gemm_choose_variant(M, N, K, bits, zq.gemm_workspace_bytes(M, N, K, bits))
+        zq.tune_clear()
+        try:
+            entry, results = autotune.tune_shape(M, N, K, bits)
+            assert len(results) >= 3 and entry["us"] == min(r["us"] for r in results)
+            nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+            assert zq.gemm_choose_variant(M, N, K, bits, nbytes) == entry["variant"]
+            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+            res = _run(zq, bits, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
+            _check(orc, res, xq, s_tok, codes, s_w, bias, "tuned %dx%dx%d" % (M, N, K))
+        finally:
+            zq.tune_clear()
+        assert zq.gemm_choose_variant(M, N, K, bits, zq.gemm_workspace_bytes(M, N, K, bits)) == base
