@@ -275,6 +275,46 @@ void zq_oracle_matmul_i32_rows(const int8_t *xq, const int8_t *wq,
     }
 }
 
+/* ---- FP16 activations x INT8 weights (the W8A16 setting of Sec. 5: the input of the
+ * QKV GeMM stays FP16, the weights are INT8 codes with group-wise scales) ---- */
+/* acc[m,n] = sum_k x[m,k] * wq[n,k] in fp64 (every product is exact in fp64);
+ * absacc (nullable) = sum_k |x[m,k]| * |wq[n,k]|, the size of the terms that were added.
+ * rows (nullable): only these rows of x, acc is then [n_rows,N]. */
+void zq_oracle_matmul_f16_i8(const uint16_t *x, const int8_t *wq, const long *rows, long n_rows,
+                             long N, long K, double *acc, double *absacc)
+{
+    #pragma omp parallel for schedule(static) collapse(2)
+    for (long i = 0; i < n_rows; ++i) {
+        for (long n = 0; n < N; ++n) {
+            const uint16_t *xr = x + (rows ? rows[i] : i) * K;
+            double s = 0.0, a = 0.0;
+            for (long k = 0; k < K; ++k) {
+                const double p = (double)half_bits_to_float(xr[k]) * (double)wq[n * K + k];
+                s += p;
+                a += fabs(p);
+            }
+            acc[i * N + n] = s;
+            if (absacc) absacc[i * N + n] = a;
+        }
+    }
+}
+
+/* ref[m,n] = acc[m,n] * s_w[n / (N/groups)] + bias[n]; mag (nullable) = |acc*s_w| + |bias|. */
+void zq_oracle_dequant_w(const double *acc, const float *s_w, long groups, const uint16_t *bias,
+                         long M, long N, double *ref, double *mag)
+{
+    const long gs = N / groups;
+    #pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) {
+        for (long n = 0; n < N; ++n) {
+            const double t = acc[m * N + n] * (double)s_w[n / gs];
+            const double b = bias ? (double)half_bits_to_float(bias[n]) : 0.0;
+            ref[m * N + n] = t + b;
+            if (mag) mag[m * N + n] = fabs(t) + fabs(b);
+        }
+    }
+}
+
 /* ---- dequantization (App. D) --------------------------------------------- */
 /* ref[m,n] = acc * s_tok[m] * s_w[n / (N/groups)] + bias[n], in fp64.
  * mag (nullable) = |acc*s_tok*s_w| + |bias|, the magnitude the relative

@@ -182,6 +182,41 @@ def matmul_i32_rows(xq, wq, rows):
     return acc
 
 
+def matmul_f16_i8(x16, wq, rows=None):
+    """FP16 activations x INT8 weight codes in fp64 -> (acc [M,N], absacc [M,N] = sum of |products|).
+    `rows` restricts the result to those rows of x."""
+    x16 = _c(x16, np.float16)
+    wq = _c(wq, np.int8)
+    M, K = x16.shape
+    N, K2 = wq.shape
+    assert K == K2
+    r = None
+    n_rows = M
+    if rows is not None:
+        r = np.ascontiguousarray(rows, dtype=np.int64)
+        assert r.min() >= 0 and r.max() < M
+        n_rows = r.size
+    acc = np.empty((n_rows, N), np.float64)
+    absacc = np.empty((n_rows, N), np.float64)
+    _load().zq_oracle_matmul_f16_i8(_p(x16), _p(wq), None if r is None else _p(r), ctypes.c_long(n_rows),
+                                    ctypes.c_long(N), ctypes.c_long(K), _p(acc), _p(absacc))
+    return acc, absacc
+
+
+def dequant_w(acc64, s_w, bias16):
+    """Weight-scale-only epilogue in fp64 (no activation scale) -> (ref, mag = |acc*s_w| + |bias|)."""
+    acc64 = _c(acc64, np.float64)
+    s_w = _c(s_w, np.float32)
+    M, N = acc64.shape
+    assert N % s_w.size == 0
+    ref = np.empty((M, N), np.float64)
+    mag = np.empty((M, N), np.float64)
+    b = _p(_c(bias16, np.float16)) if bias16 is not None else None
+    _load().zq_oracle_dequant_w(_p(acc64), _p(s_w), ctypes.c_long(s_w.size), b, ctypes.c_long(M),
+                                ctypes.c_long(N), _p(ref), _p(mag))
+    return ref, mag
+
+
 def dequant(acc, s_tok, s_w, bias16):
     """App. D epilogue in fp64 -> (ref, mag) with mag = |acc*s_tok*s_w| + |bias|."""
     acc = _c(acc, np.int32)

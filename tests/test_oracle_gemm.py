@@ -111,3 +111,49 @@ def test_quantized_linear_approximates_the_fp_linear():
     ref4, _ = orc.dequant(orc.matmul_i32(xq, codes4), s_tok, s_w4, b16)
     rel4 = np.linalg.norm(ref4 - exact) / np.linalg.norm(exact)
     assert rel < rel4 < 0.3
+
+
+def test_matmul_f16_i8_pins():
+    """FP16 x INT8 product in fp64: a Python triple loop with exact rationals, numpy float64 matmul,
+    integer-valued activations reduce to the int32 product, selector rows pick single weight columns,
+    and the row subset equals the rows of the full result."""
+    from fractions import Fraction
+    rng = zq_inputs.rng_for(8, 1)
+    M, N, K = 3, 5, 16
+    x = (rng.standard_normal((M, K)) * 3).astype(np.float16)
+    w = zq_inputs.random_codes(rng, (N, K))
+    acc, absacc = orc.matmul_f16_i8(x, w)
+    for m in range(M):
+        for n in range(N):
+            s = sum(Fraction(float(x[m, k])) * int(w[n, k]) for k in range(K))
+            a = sum(abs(Fraction(float(x[m, k])) * int(w[n, k])) for k in range(K))
+            assert acc[m, n] == float(s) and absacc[m, n] == float(a)
+    M, N, K = 9, 48, 1040
+    x = (rng.standard_normal((M, K)) * 2).astype(np.float16)
+    w = zq_inputs.random_codes(rng, (N, K))
+    acc, absacc = orc.matmul_f16_i8(x, w)
+    want = x.astype(np.float64) @ w.astype(np.float64).T
+    assert np.abs(acc - want).max() <= 1e-9 * np.abs(absacc).max()
+    assert (absacc >= np.abs(acc) - 1e-9).all()
+    xi = zq_inputs.random_codes(rng, (M, K))
+    acc_i, _ = orc.matmul_f16_i8(xi.astype(np.float16), w)          # |codes| <= 127 are exact in FP16
+    assert np.array_equal(acc_i, orc.matmul_i32(xi, w).astype(np.float64))
+    sel = np.zeros((2, K), np.float16)
+    sel[0, 7] = 1.0
+    sel[1, 1039] = -0.5
+    acc_s, _ = orc.matmul_f16_i8(sel, w)
+    assert np.array_equal(acc_s[0], w[:, 7].astype(np.float64)) and np.array_equal(acc_s[1], -0.5 * w[:, 1039])
+    sub, sub_abs = orc.matmul_f16_i8(x, w, rows=[8, 0, 3])
+    assert np.array_equal(sub, acc[[8, 0, 3]]) and np.array_equal(sub_abs, absacc[[8, 0, 3]])
+
+
+def test_dequant_w_pins():
+    acc = np.array([[2.0, -4.0] + [0.0] * 30, [1.0, 1.0] + [3.0] * 30])
+    s_w = np.array([0.5, 0.25], np.float32)
+    bias = np.zeros(32, np.float16)
+    bias[1] = 1.0
+    ref, mag = orc.dequant_w(acc, s_w, bias)
+    assert ref[0, 0] == 1.0 and ref[0, 1] == -1.0 and mag[0, 1] == 3.0
+    assert ref[1, 16] == 0.75 and ref[1, 31] == 0.75 and ref[1, 15] == 1.5
+    ref2, _ = orc.dequant_w(acc, s_w, None)
+    assert ref2[0, 1] == -2.0
