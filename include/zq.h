@@ -185,6 +185,27 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
                                        void *workspace, size_t workspace_bytes, zq_stream stream);
 
 /*
+ * W8A16 GeMM (Sec. 5: for the largest model the input of the QKV GeMM stays
+ * FP16 while the weights are INT8): FP16 activations against group-wise INT8
+ * weights (App. A.2), fp32 accumulation, weight-scale epilogue
+ *   out[m,n] = fp16( (sum_k x[m,k] * wq[n,k]) * s_w[n / (N/groups)] + bias[n] ).
+ *   x_fp16    in,  fp16 [M,K] row-major                      (device)
+ *   wq        in,  int8 [N,K];  s_w  fp32 [groups];  bias_fp16  fp16 [N] or NULL   (device)
+ *   out_fp16  out, fp16 [M,N]                                (device)
+ *   workspace scratch of zq_gemm_workspace_bytes(M, N, K, 8) bytes or NULL: lets token counts up to
+ *             64 split K across workgroups when the matrix has few rows (fp32 partials; the result
+ *             does not depend on the order in which workgroups finish)
+ * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0.  The codes are converted to
+ * FP16 exactly; the sum is accumulated in fp32 on the FP16 matrix cores, so unlike the INT8 calls
+ * the result is reproducible but not bit-defined by the inputs alone (tolerance in the tests).
+ * Calls that split K must not overlap with other GeMM calls on the same device.
+ * Errors: ZQ_ERR_NULL, ZQ_ERR_SHAPE, ZQ_ERR_ALIGN, ZQ_ERR_HIP.
+ */
+zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
+                                const void *bias_fp16, int M, int N, int K, void *out_fp16, void *workspace,
+                                size_t workspace_bytes, zq_stream stream);
+
+/*
  * Tuning and test hook: force the GeMM schedule instead of choosing it from
  * the shape (App. D picks a schedule by batch x sequence length).
  * variant < 0 restores automatic choice.  A forced schedule whose shape

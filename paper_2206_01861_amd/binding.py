@@ -17,7 +17,7 @@ SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
     "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise", "zq_quantize_tokenwise", "zq_dequantize_acc",
-    "zq_tune_set", "zq_tune_clear", "zq_tune_count",
+    "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant",
 ]
 
 
@@ -64,6 +64,8 @@ def lib():
     L.zq_quantize_tokenwise.argtypes = [vp, ci, ci, vp, vp, vp]
     L.zq_dequantize_acc.restype = ci
     L.zq_dequantize_acc.argtypes = [vp, vp, vp, ci, vp, ci, ci, vp, vp]
+    L.zq_gemm_w8a16_dequant.restype = ci
+    L.zq_gemm_w8a16_dequant.argtypes = [vp, vp, vp, ci, vp, ci, ci, ci, vp, vp, sz, vp]
     L.zq_tune_set.restype = ci
     L.zq_tune_set.argtypes = [ci] * 8
     L.zq_tune_clear.restype = None
@@ -294,4 +296,21 @@ def zq_dequantize_acc(acc, s_tok, s_w, bias_fp16=None, out=None):
         out = torch.empty((M, N), dtype=torch.float16, device=acc.device)
     _check(lib().zq_dequantize_acc(_ptr(acc), _ptr(s_tok), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N,
                                    _ptr(out), _stream()))
+    return out
+
+
+def zq_gemm_w8a16_dequant(x_fp16, wq, s_w, bias_fp16=None, workspace=None, out=None):
+    """x fp16 [M,K] x wq int8 [N,K] -> out fp16 [M,N] = (x @ wq^T) * s_w[group] + bias."""
+    _dev(x_fp16, torch.float16, "x_fp16")
+    _dev(wq, torch.int8, "wq")
+    _dev(s_w, torch.float32, "s_w")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, K = x_fp16.shape
+    N = wq.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x_fp16.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().zq_gemm_w8a16_dequant(_ptr(x_fp16), _ptr(wq), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N, K,
+                                       _ptr(out), _ptr(workspace), ws_bytes, _stream()))
     return out

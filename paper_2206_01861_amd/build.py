@@ -16,6 +16,7 @@ SOURCES = [
     "zq_gemm_simple.hip",
     "zq_gemm_skinny.hip",
     "zq_gemm_tile.hip",
+    "zq_gemm_a16.hip",
 ]
 
 # Packed FP32 instructions are kept off; everything else is plain -O3 for gfx950.

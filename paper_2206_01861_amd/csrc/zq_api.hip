@@ -172,6 +172,32 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
                        workspace_bytes, w_bits, approx_tanh ? 2 : 1, stream);
 }
 
+zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
+                                const void *bias_fp16, int M, int N, int K, void *out_fp16, void *workspace,
+                                size_t workspace_bytes, zq_stream stream) {
+    if (x_fp16 == nullptr || wq == nullptr || s_w == nullptr || out_fp16 == nullptr) return ZQ_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
+    if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
+    if ((K % 16) != 0 || K > ZQ_MAX_K) return ZQ_ERR_SHAPE;
+    if (misaligned(x_fp16) || misaligned(wq) || misaligned(s_w) || misaligned(bias_fp16) || misaligned(out_fp16) ||
+        misaligned(workspace))
+        return ZQ_ERR_ALIGN;
+    if (workspace == nullptr) workspace_bytes = 0;
+    zq::A16Args a;
+    a.x = x_fp16; a.wq = wq; a.s_w = s_w; a.groups = groups; a.bias = bias_fp16;
+    a.M = M; a.N = N; a.K = K; a.out = out_fp16; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (M <= 64 && (K % 256) == 0) {
+        // the K split is taken only when the workspace holds its fp32 partials (same size as the INT8 call's)
+        const size_t need = zq::gemm_variant_workspace(zq::kGemmSkinnySplitK, M, N, K, 8);
+        e = zq::launch_gemm_a16_stream(a, need > 0 && workspace_bytes >= need, st);
+    } else {
+        e = zq::launch_gemm_a16_simple(a, st);
+    }
+    return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
 int zq_debug_force_gemm_variant(int variant) {
     if (variant >= zq::kGemmVariantCount) variant = -1;
     return g_forced_variant.exchange(variant < 0 ? -1 : variant);

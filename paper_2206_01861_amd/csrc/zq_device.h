@@ -11,6 +11,10 @@ typedef int32_t int32x16 __attribute__((ext_vector_type(16)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
+typedef float float32x4 __attribute__((ext_vector_type(4)));
+typedef float float32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uint32x4_t __attribute__((ext_vector_type(4)));
+
 constexpr int kWave = 64;
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -95,6 +99,23 @@ __device__ __forceinline__ float gelu_tanh(float u) {
     const float v = c * fmaf(0.044715f * u * u, u, u);
     const float e = __builtin_amdgcn_exp2f(v * (2.0f * 1.44269504088896340736f));
     return u * (1.0f - __builtin_amdgcn_rcpf(1.0f + e));
+}
+
+// Eight INT8 codes (two dwords, lowest byte first) -> eight FP16 values, exactly.  A code byte with
+// its sign bit flipped is code + 128 as an unsigned byte u; under the high byte 0x64 it reads as
+// the FP16 number 1024 + u (the FP16 spacing between 1024 and 2048 is 1), and subtracting 1152
+// leaves the code.  Two XORs, four byte permutes and four packed FP16 subtractions.
+__device__ __forceinline__ half8 cvt8_i8_f16(uint32_t lo, uint32_t hi) {
+    const uint32_t ul = lo ^ 0x80808080u, uh = hi ^ 0x80808080u;
+    const uint32_t k = 0x64646464u;
+    uint32x4_t d;
+    d[0] = __builtin_amdgcn_perm(k, ul, 0x04010400u);
+    d[1] = __builtin_amdgcn_perm(k, ul, 0x04030402u);
+    d[2] = __builtin_amdgcn_perm(k, uh, 0x04010400u);
+    d[3] = __builtin_amdgcn_perm(k, uh, 0x04030402u);
+    half8 h = __builtin_bit_cast(half8, d);
+    const half_t bias = (half_t)1152.0f;
+    return h - half8{bias, bias, bias, bias, bias, bias, bias, bias};
 }
 
 // Activation fused into a GeMM epilogue: 0 none, 1 GeLU (erf form), 2 GeLU (tanh form).

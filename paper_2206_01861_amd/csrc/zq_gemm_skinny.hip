@@ -360,6 +360,214 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same streaming schedule for FP16 activations x INT8 weights (the W8A16 setting of Sec. 5:
+// the input of the QKV GeMM stays FP16).  The weight stream is unchanged (INT8 codes, so half the
+// bytes of an FP16 GeMM); each consumer converts the eight bytes of a k step to FP16 in registers
+// and multiplies with v_mfma_f32_16x16x32_f16.  The reduction index may be permuted freely as long
+// as both operands use the same order, so lane (r, j) feeds bytes 64i + 16j + 8h .. +7 of its
+// 16-byte chunk i to k step (i, h) and reads the matching eight FP16 activations, one 16-byte
+// LDS read at byte 128i + 32j + 16h of the token's 512-byte stage row.  Accumulation is fp32; with
+// a K split the last arrival adds all partials in split order, so the result does not depend on
+// arrival order.  Epilogue: acc * s_w[group] + bias (there is no activation scale).
+template <int MT, int DW, int R>
+__global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kernel(
+    const half_t *__restrict__ x, const uint8_t *__restrict__ wq, const float *__restrict__ s_w, int gs,
+    const half_t *__restrict__ bias, int M, int N, int K, half_t *__restrict__ out, float *__restrict__ partial,
+    StreamPlan plan) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int LW = 4;                             // 16-byte weight loads per lane per stage
+    constexpr int X_ROW = kStageK * 2;                // bytes of one token's stage row (FP16)
+    constexpr int X_STAGE = MT * 16 * X_ROW;          // bytes of one activation stage
+    constexpr int LX = X_STAGE / 1024;                // 1 KB direct loads per stage (producer wave)
+
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r = lane % 16;
+    const int j = lane / 16;
+
+    const int rb = (int)blockIdx.x % plan.row_blocks;
+    const int ks = (int)blockIdx.x / plan.row_blocks;
+    const int s_lo = (int)((long)rb * plan.strips / plan.row_blocks);
+    const int s_hi = (int)(((long)rb + 1) * plan.strips / plan.row_blocks);
+    const int k_lo = (int)((long)ks * plan.stages / plan.k_splits);
+    const int k_hi = (int)(((long)ks + 1) * plan.stages / plan.k_splits);
+    const int n = k_hi - k_lo;
+    const int npad = (n + DW - 1) / DW * DW;
+
+    if (wave == 0) {
+        // ---- producer: FP16 activation stages into the LDS ring --------------
+        // A 1 KB unit is 2 rows x 512 bytes; 16-byte chunk c of row m sits at position c ^ (m & 15),
+        // which makes the consumers' fragment reads (16 rows, one chunk) conflict free.
+        const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<half_t *>(x), 0, (int)((size_t)M * K * 2), kRsrcFlags);
+        int voff[LX];
+#pragma unroll
+        for (int u = 0; u < LX; ++u) {
+            const int row = u * 2 + lane / 32;
+            int grow = row;
+            if (grow > M - 1) grow = M - 1;           // rows past M: valid data, results never stored
+            voff[u] = grow * K * 2 + (((lane % 32) ^ (row & 15)) * 16);
+        }
+        auto issue_x = [&](int i, int slot) __attribute__((always_inline)) {
+            uint8_t *base = smem + slot * X_STAGE;
+            const int soff = (k_lo + i) * X_ROW;
+#pragma unroll
+            for (int u = 0; u < LX; ++u)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[u], soff, 0, 0);
+        };
+#pragma unroll
+        for (int s = 0; s < R - 1; ++s)
+            if (s < n) issue_x(s, s);
+        for (int i = 0; i < npad; ++i) {
+            if (i < n) {
+                if (i + R - 2 < n)
+                    wait_vmcnt<(R - 2) * LX>();
+                else
+                    wait_vmcnt<0>();
+            }
+            lds_barrier();
+            if (i + R - 1 < n) issue_x(i + R - 1, (i + R - 1) % R);
+        }
+        return;
+    }
+
+    const int strip = s_lo + wave - 1;
+    if (strip >= s_hi) {                              // no strip for this wave: keep the barrier count
+        for (int i = 0; i < npad; ++i) lds_barrier();
+        return;
+    }
+
+    // ---- consumers: INT8 weight strip through registers ----------------------
+    const uint32x4 rs_w = make_srd(wq, (uint32_t)((size_t)N * K));
+    const int voff_w = (int)((uint32_t)(strip * 16 + r) * (uint32_t)K + (uint32_t)(j * 16));
+    int32x4 wreg[DW][LW];
+    auto issue_w = [&](int i, int32x4(&dst)[LW]) __attribute__((always_inline)) {
+        if (i > n - 1) i = n - 1;
+        const int soff = __builtin_amdgcn_readfirstlane((k_lo + i) * kStageK);
+        stream_load16<0>(dst[0], voff_w, rs_w, soff);
+        stream_load16<64>(dst[1], voff_w, rs_w, soff);
+        stream_load16<128>(dst[2], voff_w, rs_w, soff);
+        stream_load16<192>(dst[3], voff_w, rs_w, soff);
+    };
+
+    float32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = float32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int x_lane = r * X_ROW;
+    auto compute = [&](const int32x4(&w)[LW], const uint8_t *xs) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const half8 a = cvt8_i8_f16((uint32_t)w[i][2 * h], (uint32_t)w[i][2 * h + 1]);
+                const int c = 8 * i + 2 * j + h;      // 16-byte chunk of the 512-byte row
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const half8 b = *reinterpret_cast<const half8 *>(xs + mt * 16 * X_ROW + x_lane + ((c ^ r) * 16));
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[mt], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    int i = 0;
+    auto step_compute = [&](const int32x4(&w)[LW]) __attribute__((always_inline)) {
+        if (i < n) compute(w, smem + (i % R) * X_STAGE);
+    };
+#pragma unroll
+    for (int d = 0; d < DW; ++d) issue_w(d, wreg[d]);
+    for (int grp = DW; grp < npad; grp += DW) {
+#pragma unroll
+        for (int d = 0; d < DW; ++d) {
+            stream_wait<(DW - 1) * LW, LW>(wreg[d]);
+            lds_barrier();
+            step_compute(wreg[d]);
+            issue_w(i + DW, wreg[d]);
+            ++i;
+        }
+    }
+    auto drain = [&](auto dc) __attribute__((always_inline)) {
+        constexpr int d = decltype(dc)::value;
+        if constexpr (d < DW) {
+            stream_wait<(DW - 1 - d) * LW, LW>(wreg[d]);
+            lds_barrier();
+            step_compute(wreg[d]);
+            ++i;
+        }
+    };
+    static_assert(DW <= 4, "the drain is written out for at most four stages");
+    drain(std::integral_constant<int, 0>{});
+    drain(std::integral_constant<int, 1>{});
+    drain(std::integral_constant<int, 2>{});
+    drain(std::integral_constant<int, 3>{});
+
+    // ---- K split: park the fp32 partial strip, count the arrival, last arrival adds all in order --
+    if (plan.k_splits > 1) {
+        const int nseg = plan.k_splits;
+        const size_t slot_words = (size_t)M * 16;
+        const __amdgpu_buffer_rsrc_t rs_p = __builtin_amdgcn_make_buffer_rsrc(
+            partial, 0, (int)((size_t)plan.strips * nseg * slot_words * sizeof(float)), kRsrcFlags);
+        constexpr int kNowhere = 0x7ffffff0;          // past the end of the buffer: stores dropped, loads 0
+        auto slot_off = [&](int o, int m) __attribute__((always_inline)) {
+            return (int)((((size_t)strip * nseg + o) * slot_words + (size_t)m * 16 + 4 * j) * 4);
+        };
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + r;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(int32x4, acc[mt]), rs_p,
+                                                   (m < M) ? slot_off(ks, m) : kNowhere, 0, kAuxDeviceCoherent);
+        }
+        wait_vmcnt<0>();
+        unsigned prev = 0;
+        if (lane == 0)
+            prev = __hip_atomic_fetch_add(&g_strip_arrivals[strip], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __builtin_amdgcn_readfirstlane(prev);
+        if (prev != (unsigned)nseg - 1u) return;
+        if (lane == 0)
+            __hip_atomic_store(&g_strip_arrivals[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = float32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int o0 = 0; o0 < nseg; o0 += 4) {        // every partial, this wave's included, in split order
+            float32x4 part[4][MT];
+#pragma unroll
+            for (int oo = 0; oo < 4; ++oo) {
+                const int o = o0 + oo;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = mt * 16 + r;
+                    part[oo][mt] = __builtin_bit_cast(float32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                        rs_p, (o < nseg && m < M) ? slot_off(o, m) : kNowhere, 0, kAuxDeviceCoherent));
+                }
+            }
+#pragma unroll
+            for (int oo = 0; oo < 4; ++oo)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt] += part[oo][mt];
+        }
+    }
+
+    const int n_col = strip * 16 + 4 * j;
+    const float sw = s_w[n_col / gs];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + r;
+        if (m < M) {
+            half4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float f = acc[mt][e] * sw;
+                if (bias != nullptr) f += (float)bias[n_col + e];
+                o[e] = (half_t)f;
+            }
+            *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
+        }
+    }
+#endif
+}
+
 namespace {
 
 constexpr int kCUs = 256;
@@ -458,6 +666,36 @@ void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blo
     *row_blocks = plan.row_blocks;
     *k_splits = plan.k_splits;
     *consumers = plan.consumers;
+}
+
+namespace {
+template <int MT>
+hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStream_t st) {
+    constexpr int R = 3, DW = 4;
+    constexpr size_t lds = (size_t)R * MT * 16 * kStageK * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_stream_a16_kernel<MT, DW, R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_stream_a16_kernel<MT, DW, R>), dim3(plan.row_blocks * plan.k_splits),
+                       dim3(64 * (plan.consumers + 1)), lds, st, reinterpret_cast<const half_t *>(a.x),
+                       reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
+                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
+                       reinterpret_cast<float *>(a.workspace), plan);
+    return hipGetLastError();
+}
+}  // namespace
+
+// FP16 activations: the same cut as the INT8 call of the same shape (the weight stream is the same).
+hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st) {
+    const StreamPlan plan = plan_stream(a.M, a.N, a.K, 8, allow_split);
+    const int mt = token_tiles(a.M);
+    if (mt <= 1) return launch_stream_a16_t<1>(a, plan, st);
+    if (mt <= 2) return launch_stream_a16_t<2>(a, plan, st);
+    return launch_stream_a16_t<4>(a, plan, st);
 }
 
 hipError_t launch_gemm_skinny(const GemmArgs &a, bool allow_split, hipStream_t st) {

@@ -50,6 +50,21 @@ struct GemmArgs {
 // A caller-supplied cut of the streaming schedules for this shape, if one was registered.
 bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_splits);
 
+// FP16 activations x INT8 weights (W8A16).
+struct A16Args {
+    const void *x;        // fp16 [M,K]
+    const void *wq;       // int8 [N,K]
+    const float *s_w;
+    int groups;
+    const void *bias;     // fp16 [N] or null
+    int M, N, K;
+    void *out;            // fp16 [M,N]
+    void *workspace;      // fp32 partials of the K split (same size as the INT8 call's workspace)
+    size_t workspace_bytes;
+};
+hipError_t launch_gemm_a16_simple(const A16Args &a, hipStream_t st);
+hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st);   // M <= 64, K % 256 == 0
+
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);
 hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st);

@@ -201,6 +201,23 @@ def test_tuning_table_overrides_the_choice():
     assert zq.tune_count() == 0 and zq.gemm_choose_variant(16, 4096, 4096, 8, 0) == base
 
 
+def test_w8a16_validation():
+    f = zq.lib().zq_gemm_w8a16_dequant
+
+    def call(x=P, wq=P, s_w=P, groups=4, bias=None, M=8, N=64, K=128, out=P, ws=None, ws_bytes=0):
+        return f(x, wq, s_w, groups, bias, M, N, K, out, ws, ws_bytes, None)
+
+    assert call(x=None) == E_NULL
+    assert call(wq=None) == E_NULL
+    assert call(out=None) == E_NULL
+    assert call(M=0) == E_SHAPE
+    assert call(groups=3) == E_SHAPE
+    assert call(K=136) == E_SHAPE
+    assert call(K=133152) == E_SHAPE
+    assert call(x=P + 2) == E_ALIGN
+    assert call(ws=P + 4, ws_bytes=64) == E_ALIGN
+
+
 def test_missing_library_is_an_error(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))
