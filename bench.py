@@ -329,6 +329,48 @@ def time_gemm(zq, name, M, reps_target=40):
             "fp16_us": fbest * 1e3, "speedup_vs_fp16": fbest / best, "rotating_sets": nset}
 
 
+def time_gemm_a16(zq, name, M, reps_target=40):
+    """W8A16 (FP16 activations x INT8 weights) on a QKV linear: the setting the paper uses for the input
+    of the QKV GeMM of its largest model (Sec. 5)."""
+    K, N, g, bits = zq_inputs.LINEARS[name]
+    gen = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED % (2 ** 31) + 7 * M)
+    wbytes = N * K
+    nset = int(max(1, min(32, -(-(640 << 20) // wbytes)))) if M <= 64 else 1
+    x = (torch.randn((M, K), generator=gen, device="cuda") *
+         torch.exp(torch.empty((M, 1), device="cuda").uniform_(np.log(0.5), np.log(2.0), generator=gen))).half()
+    sets = []
+    for _ in range(nset):
+        w = (torch.randn((N, K), generator=gen, device="cuda") * 0.02).half()
+        wq, sw = zq.zq_quantize_weight_groupwise(w, g, 8)
+        del w
+        sets.append((wq, sw))
+    bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    nws = zq.gemm_workspace_bytes(M, N, K, 8)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+
+    def run(i):
+        wq, sw = sets[i % nset]
+        zq.zq_gemm_w8a16_dequant(x, wq, sw, bias, workspace=ws, out=out)
+
+    reps = max(nset, reps_target // max(1, nset) * nset) if M <= 64 else 10
+    gq = graph_of(run, reps)
+    best = min(time_graph(gq, 3, reps, warm=1) for _ in range(3))
+    wfs = [torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.02
+           for _ in range(min(nset, max(1, (640 << 20) // (2 * N * K) + 1)) if M <= 64 else 1)]
+    gf = graph_of(lambda i: torch.nn.functional.linear(x, wfs[i % len(wfs)], bias), reps)
+    fbest = min(time_graph(gf, 3, reps, warm=1) for _ in range(2))
+    del wfs, gf, gq
+    ops = 2.0 * M * N * K
+    bytes_min = 2 * M * K + wbytes + 4 * g + 2 * N + 2 * M * N
+    return {"linear": name + "/w8a16", "M": M, "N": N, "K": K, "w_bits": 8, "groups": g,
+            "schedule": "stream_a16" if (M <= 64 and K % 256 == 0) else ("tile_a16" if K % 64 == 0 else "simple_a16"),
+            "us": best * 1e3, "TOPS": ops / (best * 1e-3) / 1e12, "GBs": bytes_min / (best * 1e-3) / 1e9,
+            "frac_int8_peak": None, "frac_fp16_peak": ops / (best * 1e-3) / 1e12 / 2500.0,
+            "frac_hbm_peak": bytes_min / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "fp16_us": fbest * 1e3, "speedup_vs_fp16": fbest / best, "rotating_sets": nset}
+
+
 def run_table(args):
     import paper_2206_01861_amd as zq
     zq.lib()
@@ -346,6 +388,16 @@ def run_table(args):
         print("%-8s M=%-6d %-14s %9.1f us %8.1f TOPS %8.1f GB/s  int8 %.3f hbm %.3f  fp16 %8.1f us x%.2f" % (
             name, M, r["schedule"], r["us"], r["TOPS"], r["GBs"], r["frac_int8_peak"], r["frac_hbm_peak"],
             r["fp16_us"], r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
+        torch.cuda.empty_cache()
+    # W8A16 on the QKV linears (the GeMM whose input the paper keeps in FP16 for its largest model)
+    for name, M in cases:
+        if not name.endswith("_qkv"):
+            continue
+        r = time_gemm_a16(zq, name, M)
+        rows.append(r)
+        print("%-14s M=%-4d %-11s %9.1f us %8.1f TFLOPS %8.1f GB/s  hbm %.3f  fp16 %8.1f us x%.2f" % (
+            r["linear"], M, r["schedule"], r["us"], r["TOPS"], r["GBs"], r["frac_hbm_peak"], r["fp16_us"],
+            r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
         torch.cuda.empty_cache()
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:

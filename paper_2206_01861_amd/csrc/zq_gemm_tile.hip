@@ -24,6 +24,8 @@
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
 // in that XCD's L2.
+#include <type_traits>
+
 #include "zq_device.h"
 #include "zq_internal.h"
 
@@ -68,7 +70,7 @@ struct TileCfg {
 }  // namespace
 
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
@@ -87,8 +89,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr int RPU = 64 / CPR;                    // rows per 1 KB load unit
     constexpr int XU = BM / RPU;                     // load units in the activation tile
     constexpr int WU = BN / RPU;
-    constexpr int DIRECT_UNITS = (WBITS == 8) ? (XU + WU) : XU;
+    // XT = 1: FP16 activations (W8A16).  A stage row is still BK bytes, now BK/2 values of K; the INT8
+    // weights take the register path of the INT4 weights (16 source bytes -> two 16-byte chunks) with
+    // an exact INT8 -> FP16 conversion instead of the nibble unpack, and the MFMA is the FP16 one.
+    constexpr bool STAGED_W = (WBITS == 4) || (XT == 1);
+    constexpr int XB = (XT == 1) ? 2 : 1;            // bytes per activation value
+    static_assert(XT == 0 || WBITS == 8, "FP16 activations go with INT8 weights");
+    constexpr int DIRECT_UNITS = STAGED_W ? XU : (XU + WU);
     static_assert(XU % NW == 0 && WU % NW == 0, "load units must split evenly over the waves");
+    using AccT = typename std::conditional<XT == 1, float32x16, int32x16>::type;
     constexpr int LPS = DIRECT_UNITS / NW;           // direct loads per wave per stage
     constexpr int TPR4 = BK / 32;                    // INT4: threads per row (16 packed bytes each)
     constexpr int W4_ROWS = NT / TPR4;               // rows per pass
@@ -114,10 +123,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     const int n0 = tn * BN;
 
     const int wrow_bytes = (WBITS == 8) ? K : K / 2;
+    const int xrow_bytes = K * XB;
     const __amdgpu_buffer_rsrc_t rs_w =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(wq), 0, (int)((size_t)N * wrow_bytes), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rs_x =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(xq), 0, (int)((size_t)M * K), kRsrcFlags);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(xq), 0, (int)((size_t)M * xrow_bytes), kRsrcFlags);
 
     // ---- per-lane source offsets of this wave's direct-load units ---------
     // Wave w takes units w, w+NW, ...; units below XU are activation rows, the
@@ -131,7 +141,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             const int row = u * RPU + lane / CPR;
             int grow = m0 + row;
             if (grow > M - 1) grow = M - 1;
-            voff[i] = grow * K + (((lane % CPR) ^ swz<BK>(row)) * 16);
+            voff[i] = grow * xrow_bytes + (((lane % CPR) ^ swz<BK>(row)) * 16);
         } else {
             const int row = (u - XU) * RPU + lane / CPR;
             int grow = n0 + row;
@@ -141,7 +151,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     }
     // INT4 weights: thread -> (row = pass*W4_ROWS + tid/TPR4, 16 packed bytes = 32 codes = chunks 2q, 2q+1)
     int w4_voff[W4_PASSES];
-    if (WBITS == 4) {
+    if (STAGED_W) {
 #pragma unroll
         for (int p = 0; p < W4_PASSES; ++p) {
             int grow = n0 + p * W4_ROWS + (int)threadIdx.x / TPR4;
@@ -177,10 +187,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             const int q = (int)threadIdx.x % TPR4;
             if (BN >= W4_ROWS || row < BN) {
                 uint32_t d[8];
-                unpack8_nat((uint32_t)w4_regs[p][0], d[0], d[1]);
-                unpack8_nat((uint32_t)w4_regs[p][1], d[2], d[3]);
-                unpack8_nat((uint32_t)w4_regs[p][2], d[4], d[5]);
-                unpack8_nat((uint32_t)w4_regs[p][3], d[6], d[7]);
+                if (XT == 1) {
+                    const uint32x4_t lo = __builtin_bit_cast(
+                        uint32x4_t, cvt8_i8_f16((uint32_t)w4_regs[p][0], (uint32_t)w4_regs[p][1]));
+                    const uint32x4_t hi = __builtin_bit_cast(
+                        uint32x4_t, cvt8_i8_f16((uint32_t)w4_regs[p][2], (uint32_t)w4_regs[p][3]));
+                    d[0] = lo[0]; d[1] = lo[1]; d[2] = lo[2]; d[3] = lo[3];
+                    d[4] = hi[0]; d[5] = hi[1]; d[6] = hi[2]; d[7] = hi[3];
+                } else {
+                    unpack8_nat((uint32_t)w4_regs[p][0], d[0], d[1]);
+                    unpack8_nat((uint32_t)w4_regs[p][1], d[2], d[3]);
+                    unpack8_nat((uint32_t)w4_regs[p][2], d[4], d[5]);
+                    unpack8_nat((uint32_t)w4_regs[p][3], d[6], d[7]);
+                }
                 const int s = swz<BK>(row);
                 *reinterpret_cast<int32x4 *>(base + row * BK + (((2 * q) ^ s) * 16)) =
                     int32x4{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
@@ -191,7 +210,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     };
 
     // ---- accumulators -----------------------------------------------------
-    int32x16 acc[FN][FM];
+    AccT acc[FN][FM];
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
@@ -221,7 +240,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
             for (int fm = 0; fm < FM; ++fm)
-                acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
+                if constexpr (XT == 1)
+                    acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a[fn]),
+                                                                          __builtin_bit_cast(half8, bx[fm]), acc[fn][fm], 0,
+                                                                          0, 0);
+                else
+                    acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
     };
     // one LDS read after every (FN*FM)/(FN+FM) MFMAs
     auto interleave = [&]() {
@@ -247,26 +271,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     for (int r = threadIdx.x; r < BM; r += NT) {
         int m = m0 + r;
         if (m > M - 1) m = M - 1;
-        row_scale[r] = s_tok[m];
+        row_scale[r] = (XT == 1) ? 1.0f : s_tok[m];   // FP16 activations carry no token scale
     }
 
     // ---- main loop ----------------------------------------------------------
     // Stage kt lives in slot kt % NSTAGE.  During the last k step of stage kt every wave already holds
     // that step's fragments in registers, so after the barrier there the slot is free and receives
     // stage kt + NSTAGE, while the first fragments of stage kt + 1 are read under the last MFMAs.
-    const int nkt = K / BK;
+    const int nkt = xrow_bytes / BK;
     int32x4 a0[FN], b0[FM], a1[FN], b1[FM];
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         if (s < nkt) {
             issue_direct(s, s);
-            if (WBITS == 4) {
+            if (STAGED_W) {
                 w4_fetch(s);
                 w4_store(s);
             }
         }
     }
-    if (WBITS == 8 && nkt >= NSTAGE)
+    if (!STAGED_W && nkt >= NSTAGE)
         wait_vmcnt<(NSTAGE - 1) * LPS>();      // stage 0 has landed; later stages may still be in flight
     else
         wait_vmcnt<0>();
@@ -286,18 +310,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 read_frags(sb, ks + 1, na, nb2);
                 mfma_step(ca, cb);
                 interleave();
-                if (WBITS == 4 && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < nkt)
+                if (STAGED_W && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < nkt)
                     w4_store((kt + NSTAGE - 1) % NSTAGE);     // registers fetched at the previous stage boundary
             } else {
                 if (kt + 1 < nkt) {
-                    if (WBITS == 8 && kt + NSTAGE - 1 < nkt)
+                    if (!STAGED_W && kt + NSTAGE - 1 < nkt)
                         wait_vmcnt<(NSTAGE - 2) * LPS>();     // stage kt+1 has landed
                     else
                         wait_vmcnt<0>();
                     lds_barrier();
                     if (kt + NSTAGE < nkt) {
                         issue_direct(kt + NSTAGE, kt % NSTAGE);
-                        if (WBITS == 4) w4_fetch(kt + NSTAGE);
+                        if (STAGED_W) w4_fetch(kt + NSTAGE);
                     }
                     read_frags(sn, 0, na, nb2);
                 }
@@ -326,14 +350,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 const int nl = fn * 32 + 8 * q + 4 * lc;
                 const float4 sc = *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
                 const float4 cb = *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
-                int32x4 v = {acc[fn][fm][4 * q], acc[fn][fm][4 * q + 1], acc[fn][fm][4 * q + 2],
-                             acc[fn][fm][4 * q + 3]};
-                if (WBITS == 4) {
+                int32x4 v = {0, 0, 0, 0};
+                float fv[4];
+                if constexpr (XT == 1) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
+                    for (int e = 0; e < 4; ++e) fv[e] = acc[fn][fm][4 * q + e];
+                } else {
+                    v = int32x4{acc[fn][fm][4 * q], acc[fn][fm][4 * q + 1], acc[fn][fm][4 * q + 2],
+                                acc[fn][fm][4 * q + 3]};
+                    if (WBITS == 4) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) fv[e] = (float)v[e];
                 }
-                float f[4] = {(float)v[0] * (st * sc.x) + cb.x, (float)v[1] * (st * sc.y) + cb.y,
-                              (float)v[2] * (st * sc.z) + cb.z, (float)v[3] * (st * sc.w) + cb.w};
+                float f[4] = {fv[0] * (st * sc.x) + cb.x, fv[1] * (st * sc.y) + cb.y,
+                              fv[2] * (st * sc.z) + cb.z, fv[3] * (st * sc.w) + cb.w};
                 if (act != 0) {                   // wave-uniform
 #pragma unroll
                     for (int e = 0; e < 4; ++e) f[e] = apply_activation(f[e], act);
@@ -342,7 +375,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
                 *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
-                if (acc_out != nullptr) {
+                if (XT == 0 && acc_out != nullptr) {
                     const int m = mw + fm * 32 + lr;
                     if (m < M && nw + nl < N) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
                 }
@@ -365,20 +398,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 
 namespace {
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0>
 hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st) {
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     constexpr size_t lds = Cfg::kLds;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS>),
+            reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS>), dim3(tiles_m * tiles_n),
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT>), dim3(tiles_m * tiles_n),
                        dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq), a.s_w,
                        a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
                        reinterpret_cast<half_t *>(a.out), a.acc_out, tiles_m, tiles_n, a.act);
@@ -407,6 +440,20 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     }
     if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 64, 4, 8>(a, st);
     return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
+}
+
+// FP16 activations x INT8 weights on the tiled schedules (K % 64 == 0).  The argument block is the
+// INT8 one with xq pointing at the FP16 activations and no token scales.
+hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
+    GemmArgs a;
+    a.xq = reinterpret_cast<const int8_t *>(a16.x);
+    a.s_tok = nullptr;
+    a.wq = a16.wq; a.s_w = a16.s_w; a.groups = a16.groups; a.bias = a16.bias;
+    a.M = a16.M; a.N = a16.N; a.K = a16.K; a.out = a16.out; a.acc_out = nullptr;
+    a.workspace = nullptr; a.workspace_bytes = 0; a.w_bits = 8; a.act = 0;
+    const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+    if (t256 >= 160) return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 1>(a, st);
+    return launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1>(a, st);
 }
 
 }  // namespace zq

@@ -64,6 +64,7 @@ struct A16Args {
 };
 hipError_t launch_gemm_a16_simple(const A16Args &a, hipStream_t st);
 hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st);   // M <= 64, K % 256 == 0
+hipError_t launch_gemm_a16_tile(const A16Args &a, hipStream_t st);                       // K % 64 == 0
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);

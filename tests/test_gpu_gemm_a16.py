@@ -35,6 +35,8 @@ SHAPES = [
     # ... the streaming schedule, one to four token tiles, uneven strips ...
     (1, 64, 256, 4), (8, 6144, 2048, 128), (33, 144, 1792, 9), (64, 1024, 1536, 64), (16, 33040, 512, 5),
     (50, 16, 256, 1),
+    # ... the tiled schedules (128x128 and 256x256 tiles, ragged edges) ...
+    (300, 400, 384, 25), (515, 1024, 1024, 64), (129, 272, 2048, 17), (2500, 4112, 512, 257),
     # ... and with a K split
     (32, 2048, 8192, 128), (7, 528, 24576, 11), (64, 4112, 16384, 1), (1, 2048, 8192, 128),
 ]
@@ -77,7 +79,7 @@ def test_w8a16_integer_inputs_are_exact(zq, orc):
     assert np.array_equal(host(out).view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("name,M", [("c5_qkv", 64), ("c4_qkv", 16), ("c3_qkv", 1)])
+@pytest.mark.parametrize("name,M", [("c5_qkv", 64), ("c4_qkv", 16), ("c3_qkv", 1), ("c3_qkv", 2048), ("c4_qkv", 4096)])
 def test_w8a16_full_size_sampled_rows(zq, orc, name, M):
     """QKV linears at workload size in the launch configuration the benchmark times; sampled rows."""
     K, N, g, bits = zq_inputs.LINEARS[name]
@@ -91,5 +93,5 @@ def test_w8a16_full_size_sampled_rows(zq, orc, name, M):
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
     out = zq.zq_gemm_w8a16_dequant(x, codes, s_w, bias, workspace=ws)
     torch.cuda.synchronize()
-    rows = sorted(set([0, M - 1, M // 2, min(M - 1, 15), min(M - 1, 16)]))
+    rows = sorted(set([0, M - 1, M // 2, min(M - 1, 15), min(M - 1, 16), min(M - 1, 255), min(M - 1, 256)]))
     _check(orc, host(out), host(x), host(codes), host(s_w), host(bias), "w8a16 %s M=%d" % (name, M), rows=rows)
