@@ -636,13 +636,9 @@ hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_
     constexpr int R = 3;
     constexpr int DW = (WBITS == 8) ? 4 : 8;
     constexpr size_t lds = (size_t)R * MT * 16 * kStageK;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    const void *kernel = reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R>);
+    if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks * plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq),
                        a.s_w, a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
@@ -673,13 +669,9 @@ template <int MT>
 hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStream_t st) {
     constexpr int R = 3, DW = 4;
     constexpr size_t lds = (size_t)R * MT * 16 * kStageK * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_stream_a16_kernel<MT, DW, R>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    const void *kernel = reinterpret_cast<const void *>(&gemm_stream_a16_kernel<MT, DW, R>);
+    if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     hipLaunchKernelGGL((gemm_stream_a16_kernel<MT, DW, R>), dim3(plan.row_blocks * plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, reinterpret_cast<const half_t *>(a.x),
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,

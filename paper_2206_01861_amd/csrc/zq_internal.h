@@ -5,7 +5,23 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace zq {
+
+// Raise a kernel's dynamic LDS limit once per device (the attribute is per device; a process may
+// drive several).  `done` is the caller's per-kernel bit mask of devices already configured.
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_relaxed) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    done.fetch_or(bit, std::memory_order_relaxed);
+    return hipSuccess;
+}
 
 enum RowOp { kOpLayerNorm = 0, kOpGeluErf = 1, kOpGeluTanh = 2, kOpIdentity = 3 };
 
