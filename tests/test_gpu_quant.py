@@ -165,3 +165,24 @@ def test_standalone_dequantizer(zq, orc, M, N, g):
     torch.cuda.synchronize()
     d = (o.float() - o2.float()).abs()
     assert bool((d <= o.float().abs() * 2.0 ** -10 + 2.0 ** -24).all())
+
+
+def test_kernels_reproduce_the_frozen_small_case(zq):
+    """The stored oracle outputs of tests/golden/quantizer_small.txt, reproduced by the HIP kernels bit for bit."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "quantizer_small.txt")
+    rec = dict(line.split(" ", 1) for line in open(path).read().splitlines() if not line.startswith("#"))
+    w = np.frombuffer(bytes.fromhex(rec["w_fp16_hex"]), np.float16).reshape(32, 32)
+    x = np.frombuffer(bytes.fromhex(rec["x_fp16_hex"]), np.float16).reshape(4, 32)
+    for bits in (8, 4):
+        wq, s_w = zq.zq_quantize_weight_groupwise(dev(w.copy()), 2, bits)
+        torch.cuda.synchronize()
+        assert host(wq).view(np.uint8).tobytes().hex() == rec["w%d_packed_hex" % bits]
+        assert host(s_w).view(np.uint32).tobytes().hex() == rec["w%d_scale_hex" % bits]
+    xq, s_tok = zq.zq_quantize_tokenwise(dev(x.copy()))
+    wq8, s_w8 = zq.zq_quantize_weight_groupwise(dev(w.copy()), 2, 8)
+    _, acc, _, _ = zq.zq_gemm_i8_dequant(xq, s_tok, wq8, s_w8, None, want_acc=True)
+    torch.cuda.synchronize()
+    assert host(xq).view(np.uint8).tobytes().hex() == rec["x_codes_hex"]
+    assert host(s_tok).view(np.uint32).tobytes().hex() == rec["x_scale_hex"]
+    assert " ".join(str(int(v)) for v in host(acc).ravel()) == rec["acc_i32"]

@@ -209,3 +209,18 @@ def test_groupwise_rejects_bad_arguments():
         orc.quantize_weight_groupwise(w, 3, 8)
     with pytest.raises(ValueError):
         orc.quantize_weight_groupwise(w, 2, 5)
+
+
+def test_oracle_matches_its_frozen_small_case():
+    """tests/golden/quantizer_small.txt was written by tests/golden/make_quantizer_golden.py from
+    oracle/ alone; the paper prints no worked example, so this only guards against unnoticed
+    changes to the oracle's arithmetic."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_quantizer_golden", os.path.join(here, "make_quantizer_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "quantizer_small.txt")) as f:
+        stored = f.read().splitlines()
+    assert stored == mod.lines()
