@@ -113,7 +113,8 @@ size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
  *   out[m,n] = fp16( float(acc) * s_tok[m] * s_w[n / (N/groups)] + bias[n] )
  *   xq int8 [M,K]; s_tok fp32 [M]; wq int8 [N,K]; s_w fp32 [groups];
  *   bias_fp16 [N] or NULL; out_fp16 [M,N].
- *   Requires N % groups == 0, (N/groups) % 16 == 0, K % 16 == 0, K <= ZQ_MAX_K.
+ *   Requires N % groups == 0, (N/groups) % 16 == 0, K % 16 == 0, K <= ZQ_MAX_K,
+ *   and each operand (xq, wq) below 2 GiB (32-bit buffer offsets in the kernels).
  *   acc_out   NULL, or int32 [M,N] receiving the accumulator (parity tap).
  *   out_q / out_s_tok  both NULL, or int8 [M,N] / fp32 [M]: the token-wise
  *             quantization of the FP16-rounded `out`, ready for the next GeMM.

@@ -12,6 +12,7 @@ std::atomic<int> g_forced_variant{-1};
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 constexpr int kMaxRow = 32768;   // longest row the fused front-ends keep in registers
+constexpr uint64_t kMaxOperandBytes = 1ull << 31;   // a GeMM operand must stay below 2 GiB
 
 zq_status check_rowquant(const void *in, const void *p0, const void *p1, int M, int K, const int8_t *xq,
                          const float *s_tok, const void *y_out, int y_dtype) {
@@ -33,6 +34,8 @@ zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, cons
     if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
     if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
     if ((K % (w_bits == 4 ? 32 : 16)) != 0 || K > ZQ_MAX_K) return ZQ_ERR_SHAPE;
+    // the kernels address both operands through 32-bit buffer offsets
+    if ((uint64_t)M * K >= kMaxOperandBytes || (uint64_t)N * K * w_bits / 8 >= kMaxOperandBytes) return ZQ_ERR_SHAPE;
     if (out_q != nullptr && N > kMaxRow) return ZQ_ERR_SHAPE;
     if (misaligned(xq) || misaligned(s_tok) || misaligned(wq) || misaligned(s_w) || misaligned(bias) ||
         misaligned(out) || misaligned(acc_out) || misaligned(out_q) || misaligned(out_s_tok) ||
@@ -179,6 +182,7 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
     if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
     if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
     if ((K % 16) != 0 || K > ZQ_MAX_K) return ZQ_ERR_SHAPE;
+    if ((uint64_t)M * K * 2 >= kMaxOperandBytes || (uint64_t)N * K >= kMaxOperandBytes) return ZQ_ERR_SHAPE;
     if (misaligned(x_fp16) || misaligned(wq) || misaligned(s_w) || misaligned(bias_fp16) || misaligned(out_fp16) ||
         misaligned(workspace))
         return ZQ_ERR_ALIGN;

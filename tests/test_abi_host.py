@@ -124,6 +124,8 @@ def test_gemm_validation(fname, kmul):
     assert call(groups=8) == E_SHAPE               # 8 columns per group
     assert call(K=128 + kmul // 2) == E_SHAPE
     assert call(K=133152) == E_SHAPE               # INT32 accumulator could wrap
+    assert call(M=65536, K=32768) == E_SHAPE       # an operand of 2 GiB: beyond the 32-bit buffer offsets
+    assert call(N=65536 * (2 if kmul == 32 else 1), K=32768, groups=64) == E_SHAPE
     assert call(bias=P + 2) == E_ALIGN
     prev = zq.force_gemm_variant(2)
     try:
