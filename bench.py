@@ -15,7 +15,7 @@ timed on the host cores.
 `python bench.py --table` instead times every linear of every workload shape
 (prefill: TOPS against the INT8 matrix-core peak; decode: GB/s against HBM,
 with buffers rotated through more than 512 MB so the Infinity Cache cannot
-serve them) and writes gpurun_out/bench_table.json; the table goes to stderr.
+serve them), writes the rows as JSON to the file given by --table-json and prints the table to stderr.
 """
 import argparse
 import json
@@ -399,8 +399,9 @@ def run_table(args):
             r["linear"], M, r["schedule"], r["us"], r["TOPS"], r["GBs"], r["frac_hbm_peak"], r["fp16_us"],
             r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
         torch.cuda.empty_cache()
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+    path = os.path.abspath(args.table_json)
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
         json.dump(rows, f, indent=1)
 
 
@@ -409,7 +410,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--table", action="store_true", help="time every workload shape; writes gpurun_out/bench_table.json")
+    ap.add_argument("--table", action="store_true", help="time every workload shape")
+    ap.add_argument("--table-json", default=os.path.join(ROOT, "bench_table.json"),
+                    help="with --table: where the rows are written as JSON")
     ap.add_argument("--only", default="", help="with --table: restrict to linears whose name starts with this")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-fused", action="store_true",
