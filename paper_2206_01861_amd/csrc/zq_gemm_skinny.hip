@@ -122,9 +122,11 @@ __device__ unsigned int g_strip_arrivals[kMaxSharedStrips];
 struct StreamPlan {
     int strips;       // 16-row strips of the weight matrix (N / 16)
     int stages;       // stages of 256 K-values (K / 256)
-    int row_blocks;   // workgroups along N; block b owns strips [b*strips/row_blocks, (b+1)*strips/row_blocks)
-    int k_splits;     // workgroups along K; split s owns stages [s*stages/k_splits, (s+1)*stages/k_splits)
+    int row_blocks;   // workgroups along N; the strips are dealt out as evenly as whole strips allow
+    int k_splits;     // workgroups along K; the stages likewise
     int consumers;    // consumer waves per workgroup = most strips in a row block
+    // filled by finish_plan(): strips / row_blocks, strips % row_blocks, stages / k_splits, stages % k_splits
+    int strips_per_block, strips_rem, stages_per_split, stages_rem;
 };
 
 template <int MT, int WBITS, int DW, int R>
@@ -144,12 +146,14 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int r = lane % 16;
     const int j = lane / 16;
 
-    const int rb = (int)blockIdx.x % plan.row_blocks;
-    const int ks = (int)blockIdx.x / plan.row_blocks;
-    const int s_lo = (int)((long)rb * plan.strips / plan.row_blocks);
-    const int s_hi = (int)(((long)rb + 1) * plan.strips / plan.row_blocks);
-    const int k_lo = (int)((long)ks * plan.stages / plan.k_splits);
-    const int k_hi = (int)(((long)ks + 1) * plan.stages / plan.k_splits);
+    // blockIdx.x = row block, blockIdx.y = K split; the first `rem` blocks of each kind take one more
+    // strip / stage (the quotients come from the host: no integer division at the head of the kernel)
+    const int rb = (int)blockIdx.x;
+    const int ks = (int)blockIdx.y;
+    const int s_lo = rb * plan.strips_per_block + (rb < plan.strips_rem ? rb : plan.strips_rem);
+    const int s_hi = s_lo + plan.strips_per_block + (rb < plan.strips_rem ? 1 : 0);
+    const int k_lo = ks * plan.stages_per_split + (ks < plan.stages_rem ? ks : plan.stages_rem);
+    const int k_hi = k_lo + plan.stages_per_split + (ks < plan.stages_rem ? 1 : 0);
     const int n = k_hi - k_lo;                        // stages of this workgroup (>= 1: k_splits <= stages)
     const int npad = (n + DW - 1) / DW * DW;          // the pipeline always runs whole groups of DW
 
@@ -387,12 +391,14 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
     const int r = lane % 16;
     const int j = lane / 16;
 
-    const int rb = (int)blockIdx.x % plan.row_blocks;
-    const int ks = (int)blockIdx.x / plan.row_blocks;
-    const int s_lo = (int)((long)rb * plan.strips / plan.row_blocks);
-    const int s_hi = (int)(((long)rb + 1) * plan.strips / plan.row_blocks);
-    const int k_lo = (int)((long)ks * plan.stages / plan.k_splits);
-    const int k_hi = (int)(((long)ks + 1) * plan.stages / plan.k_splits);
+    // blockIdx.x = row block, blockIdx.y = K split; the first `rem` blocks of each kind take one more
+    // strip / stage (the quotients come from the host: no integer division at the head of the kernel)
+    const int rb = (int)blockIdx.x;
+    const int ks = (int)blockIdx.y;
+    const int s_lo = rb * plan.strips_per_block + (rb < plan.strips_rem ? rb : plan.strips_rem);
+    const int s_hi = s_lo + plan.strips_per_block + (rb < plan.strips_rem ? 1 : 0);
+    const int k_lo = ks * plan.stages_per_split + (ks < plan.stages_rem ? ks : plan.stages_rem);
+    const int k_hi = k_lo + plan.stages_per_split + (ks < plan.stages_rem ? 1 : 0);
     const int n = k_hi - k_lo;
     const int npad = (n + DW - 1) / DW * DW;
 
@@ -628,6 +634,10 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     if (best.row_blocks == 0) {                       // cannot happen (c = 1, no split is always admissible)
         best = StreamPlan{S, St, S, 1, 1};
     }
+    best.strips_per_block = S / best.row_blocks;
+    best.strips_rem = S % best.row_blocks;
+    best.stages_per_split = St / best.k_splits;
+    best.stages_rem = St % best.k_splits;
     return best;
 }
 
@@ -639,7 +649,7 @@ hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_
     static std::atomic<uint64_t> configured{0};
     const void *kernel = reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks * plan.k_splits),
+    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks, plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq),
                        a.s_w, a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
                        reinterpret_cast<half_t *>(a.out), a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan, a.act);
@@ -672,7 +682,7 @@ hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStre
     static std::atomic<uint64_t> configured{0};
     const void *kernel = reinterpret_cast<const void *>(&gemm_stream_a16_kernel<MT, DW, R>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_stream_a16_kernel<MT, DW, R>), dim3(plan.row_blocks * plan.k_splits),
+    hipLaunchKernelGGL((gemm_stream_a16_kernel<MT, DW, R>), dim3(plan.row_blocks, plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, reinterpret_cast<const half_t *>(a.x),
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
