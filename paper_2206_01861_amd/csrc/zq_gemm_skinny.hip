@@ -103,6 +103,14 @@ __device__ __forceinline__ void stream_load16(int32x4 &dst, int voff, uint32x4 s
                  : "v"(voff), "s"(srd), "s"(soff), "n"(IMM));
 }
 
+// One dword fetched the same way (used for the operands of the epilogue): issued here, not tracked
+// by the compiler, usable only after a wait followed by landed().
+__device__ __forceinline__ void async_load_dword(uint32_t &dst, const void *p) {
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p));
+}
+// After a wait that covers it: from here on the register holds the loaded value.
+__device__ __forceinline__ void landed(uint32_t &v) { asm volatile("" : "+v"(v)); }
+
 template <int N, int LW>
 __device__ __forceinline__ void stream_wait(int32x4 (&w)[LW]) {
     if (LW == 4)
@@ -276,6 +284,23 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
             ++i;
         }
     }
+    // The operands of the epilogue are fetched now, under the last stages of the stream; otherwise
+    // their L2 round trip would sit between the last MFMA and the first store.  Being younger than
+    // every weight load still in flight they only make the waits of the drain a little stricter
+    // than needed; the last of those waits (vmcnt(0)) covers them.
+    const int n_col = strip * 16 + 4 * j;
+    uint32_t sw_bits, st_bits[MT], bias_lo, bias_hi;
+    async_load_dword(sw_bits, s_w + n_col / gs);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + r;
+        async_load_dword(st_bits[mt], s_tok + (m < M ? m : M - 1));
+    }
+    // four FP16 bias values; without a bias the loads read a valid dummy address, so that no register
+    // with a load in flight ever meets a compiler-made copy at a control-flow merge
+    async_load_dword(bias_lo, bias != nullptr ? static_cast<const void *>(bias + n_col) : s_w);
+    async_load_dword(bias_hi, bias != nullptr ? static_cast<const void *>(bias + n_col + 2) : s_w);
+
     auto drain = [&](auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         if constexpr (d < DW) {
@@ -294,6 +319,13 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     drain(std::integral_constant<int, 5>{});
     drain(std::integral_constant<int, 6>{});
     drain(std::integral_constant<int, 7>{});
+
+    landed(sw_bits);                                  // the drain ended with vmcnt(0)
+    landed(bias_lo);
+    landed(bias_hi);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) landed(st_bits[mt]);
+    const float sw = __uint_as_float(sw_bits);
 
     if (WBITS == 4) {
 #pragma unroll
@@ -343,18 +375,17 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     }
 
     // ---- dequantize this wave's 16 x (MT*16) strip and write it (App. D epilogue) ---------------
-    const int n_col = strip * 16 + 4 * j;
-    const float sw = s_w[n_col / gs];
+    const half4 bias4 = __builtin_bit_cast(half4, uint2{bias_lo, bias_hi});   // zeros without a bias
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r;
         if (m < M) {
-            const float sc = s_tok[m] * sw;
+            const float sc = __uint_as_float(st_bits[mt]) * sw;
             half4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float f = (float)acc[mt][e] * sc;
-                if (bias != nullptr) f += (float)bias[n_col + e];
+                if (bias != nullptr) f += (float)bias4[e];
                 o[e] = (half_t)apply_activation(f, act);
             }
             *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
@@ -495,6 +526,13 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
             ++i;
         }
     }
+    // epilogue operands fetched under the last stages of the stream (see the INT8 kernel)
+    const int n_col = strip * 16 + 4 * j;
+    uint32_t sw_bits, bias_lo, bias_hi;
+    async_load_dword(sw_bits, s_w + n_col / gs);
+    async_load_dword(bias_lo, bias != nullptr ? static_cast<const void *>(bias + n_col) : s_w);
+    async_load_dword(bias_hi, bias != nullptr ? static_cast<const void *>(bias + n_col + 2) : s_w);
+
     auto drain = [&](auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         if constexpr (d < DW) {
@@ -509,6 +547,11 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
     drain(std::integral_constant<int, 1>{});
     drain(std::integral_constant<int, 2>{});
     drain(std::integral_constant<int, 3>{});
+
+    landed(sw_bits);                                  // the drain ended with vmcnt(0)
+    landed(bias_lo);
+    landed(bias_hi);
+    const float sw = __uint_as_float(sw_bits);
 
     // ---- K split: park the fp32 partial strip, count the arrival, last arrival adds all in order --
     if (plan.k_splits > 1) {
@@ -555,8 +598,7 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
         }
     }
 
-    const int n_col = strip * 16 + 4 * j;
-    const float sw = s_w[n_col / gs];
+    const half4 bias4 = __builtin_bit_cast(half4, uint2{bias_lo, bias_hi});
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r;
@@ -565,7 +607,7 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float f = acc[mt][e] * sw;
-                if (bias != nullptr) f += (float)bias[n_col + e];
+                if (bias != nullptr) f += (float)bias4[e];
                 o[e] = (half_t)f;
             }
             *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
