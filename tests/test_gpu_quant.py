@@ -186,3 +186,30 @@ def test_kernels_reproduce_the_frozen_small_case(zq):
     assert host(xq).view(np.uint8).tobytes().hex() == rec["x_codes_hex"]
     assert host(s_tok).view(np.uint32).tobytes().hex() == rec["x_scale_hex"]
     assert " ".join(str(int(v)) for v in host(acc).ravel()) == rec["acc_i32"]
+
+
+def test_front_ends_at_workload_size(zq, orc):
+    """LayerNorm+quant and GeLU+quant on the full 4096-token BERT-large tensors the benchmark times:
+    codes and scales bit-exact given the fp32 tap for every element, fused values against the fp64
+    chain on sampled rows."""
+    rng = zq_inputs.rng_for(2, 11)
+    M, H, F = 4096, 1024, 4096
+    x = zq_inputs.config_activations("c2", rng, M, H)
+    gamma, beta = zq_inputs.layernorm_params(rng, H)
+    xq, s_tok, y = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), dev(beta), 1e-5, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    q_o, s_o = orc.quant_tokenwise(host(y))
+    assert_bit_equal(host(s_tok), s_o, "LN s_tok")
+    assert_bit_equal(host(xq), q_o, "LN codes")
+    rows = [0, 1, 255, 256, 2047, 4095]
+    y64, _ = orc.layernorm(x[rows], gamma, beta, 1e-5)
+    check_fused_codes(host(xq)[rows], host(s_tok)[rows], host(y)[rows], y64, "LN 4096x1024")
+
+    h = (zq_inputs.activations(rng, M, F, outlier_frac=0.01, outlier_scale=6.0).astype(np.float32) * 1.5).astype(np.float16)
+    hq, s2, y2 = zq.zq_gelu_quant_tokenwise(dev(h), None, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    q_o, s_o = orc.quant_tokenwise(host(y2))
+    assert_bit_equal(host(s2), s_o, "GeLU s_tok")
+    assert_bit_equal(host(hq), q_o, "GeLU codes")
+    g64, _ = orc.gelu(h[rows], None)
+    check_fused_codes(host(hq)[rows], host(s2)[rows], host(y2)[rows], g64, "GeLU 4096x4096")
