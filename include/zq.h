@@ -196,8 +196,8 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
  *   workspace scratch of zq_gemm_workspace_bytes(M, N, K, 8) bytes or NULL: lets token counts up to
  *             64 split K across workgroups when the matrix has few rows (fp32 partials; the result
  *             does not depend on the order in which workgroups finish)
- * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (the tuned schedules need
- * K % 256 == 0 up to 64 tokens and K % 64 == 0 above; other shapes run an untiled schedule).  The codes are converted to
+ * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (up to 64 tokens the streaming
+ * schedule needs K % 256 == 0; other small shapes run an untiled schedule).  The codes are converted to
  * FP16 exactly; the sum is accumulated in fp32 on the FP16 matrix cores, so unlike the INT8 calls
  * the result is reproducible but not bit-defined by the inputs alone (tolerance in the tests).
  * Calls that split K must not overlap with other GeMM calls on the same device.

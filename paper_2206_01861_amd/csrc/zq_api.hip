@@ -196,7 +196,7 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
         // the K split is taken only when the workspace holds its fp32 partials (same size as the INT8 call's)
         const size_t need = zq::gemm_variant_workspace(zq::kGemmSkinnySplitK, M, N, K, 8);
         e = zq::launch_gemm_a16_stream(a, need > 0 && workspace_bytes >= need, st);
-    } else if ((K % 64) == 0 && (long)M * N * K > (1L << 27)) {
+    } else if ((long)M * N * K > (1L << 27)) {
         e = zq::launch_gemm_a16_tile(a, st);
     } else {
         e = zq::launch_gemm_a16_simple(a, st);

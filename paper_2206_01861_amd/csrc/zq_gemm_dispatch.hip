@@ -59,7 +59,7 @@ bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t 
         case kGemmTile128:
         case kGemmTile256:
         case kGemmTile256x128:
-            return (K % 128) == 0;
+            return true;                              // the last stage of a ragged K is zero filled
         case kGemmSkinny:
             return M <= kStreamMaxTokens && (K % 256) == 0;
         case kGemmSkinnySplitK:
@@ -98,7 +98,6 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
         if (gemm_variant_supports(kGemmSkinny, M, N, K, w_bits, 0)) return kGemmSkinny;
         if (M <= 64) return kGemmSimple;
     }
-    if ((K % 128) != 0) return kGemmSimple;
     // Tiny problems (a BERT-base layer at 128 tokens) are all latency: one wave per 16x16 tile straight
     // from global memory starts and finishes sooner than a handful of LDS-tiled workgroups (6.2 vs 6.8 us).
     if ((long)M * N * K <= (1L << 27)) return kGemmSimple;

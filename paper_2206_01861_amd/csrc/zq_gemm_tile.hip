@@ -149,6 +149,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             voff[i] = grow * wrow_bytes + (((lane % CPR) ^ swz<BK>(row)) * 16);
         }
     }
+    // K need not be a multiple of the stage depth: in the last stage the chunks past the end of a
+    // row are fetched from an offset beyond the buffer, which the hardware answers with zeros (a
+    // plain offset would run into the next row); zero operands add nothing to the product.
+    constexpr int kNowhere = 0x7ffffff0;
+    const int tail_bytes = xrow_bytes % BK;           // valid bytes of the last stage row, 0 = full
+    int voff_tail[LPS];
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+        const int u = wave + NW * i;
+        const int row = ((i < XU / NW) ? u : (u - XU)) * RPU + lane / CPR;
+        const int chunk = (lane % CPR) ^ swz<BK>(row);
+        voff_tail[i] = (tail_bytes == 0 || chunk * 16 < tail_bytes) ? voff[i] : kNowhere;
+    }
     // INT4 weights: thread -> (row = pass*W4_ROWS + tid/TPR4, 16 packed bytes = 32 codes = chunks 2q, 2q+1)
     int w4_voff[W4_PASSES];
     if (STAGED_W) {
@@ -160,24 +173,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         }
     }
 
+    const int nkt = (xrow_bytes + BK - 1) / BK;
     auto issue_direct = [&](int kt, int slot) {
         uint8_t *base = smem + slot * STAGE;
+        const bool last = kt == nkt - 1;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             const int u = wave + NW * i;
+            const int vo = last ? voff_tail[i] : voff[i];
             if (i < XU / NW)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[i], kt * BK, 0,
-                                                         0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, vo, kt * BK, 0, 0);
             else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_void *)(base + X_STAGE + (u - XU) * 1024), 16,
-                                                         voff[i], kt * BK, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_void *)(base + X_STAGE + (u - XU) * 1024), 16, vo,
+                                                         kt * BK, 0, 0);
         }
     };
     int32x4 w4_regs[W4_PASSES];
     auto w4_fetch = [&](int kt) {
 #pragma unroll
-        for (int p = 0; p < W4_PASSES; ++p)
-            w4_regs[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, w4_voff[p], kt * (BK / 2), 0);
+        for (int p = 0; p < W4_PASSES; ++p) {
+            const bool inside = kt * (BK / 2) + ((int)threadIdx.x % TPR4) * 16 < wrow_bytes;
+            w4_regs[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, inside ? w4_voff[p] : kNowhere, kt * (BK / 2), 0);
+        }
     };
     auto w4_store = [&](int slot) {
         uint8_t *base = smem + slot * STAGE + X_STAGE;
@@ -278,7 +295,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // Stage kt lives in slot kt % NSTAGE.  During the last k step of stage kt every wave already holds
     // that step's fragments in registers, so after the barrier there the slot is free and receives
     // stage kt + NSTAGE, while the first fragments of stage kt + 1 are read under the last MFMAs.
-    const int nkt = xrow_bytes / BK;
     int32x4 a0[FN], b0[FM], a1[FN], b1[FM];
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {

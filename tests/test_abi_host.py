@@ -45,7 +45,8 @@ def test_variant_table():
     # decode shapes go to a weight-streaming schedule, prefill shapes to a tiled one
     assert zq.gemm_variant_name(zq.gemm_choose_variant(1, 6144, 2048)).startswith("skinny")
     assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 4096, 1024)).startswith("tile")
-    assert zq.gemm_variant_name(zq.gemm_choose_variant(128, 768, 784)) == "simple"   # K not a multiple of 128
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(128, 768, 784)) == "simple"   # tiny: untiled
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 768, 784)).startswith("tile")   # ragged K is tiled too
     ws = zq.gemm_workspace_bytes(64, 6144, 24576)
     assert ws > 0 and ws % (64 * 6144 * 4) == 0
     assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws)) == "skinny_splitk"
@@ -127,9 +128,9 @@ def test_gemm_validation(fname, kmul):
     assert call(M=65536, K=32768) == E_SHAPE       # an operand of 2 GiB: beyond the 32-bit buffer offsets
     assert call(N=65536 * (2 if kmul == 32 else 1), K=32768, groups=64) == E_SHAPE
     assert call(bias=P + 2) == E_ALIGN
-    prev = zq.force_gemm_variant(2)
+    prev = zq.force_gemm_variant(3)
     try:
-        assert call(K=kmul * 3) == E_UNSUP         # forced tiled schedule cannot take this K
+        assert call(K=kmul * 3) == E_UNSUP         # forced streaming schedule steps K by 256: nothing is launched
     finally:
         zq.force_gemm_variant(prev)
     assert zq.force_gemm_variant(-1) == -1

@@ -68,6 +68,9 @@ SHAPES = [
     (TILE128, 1, 16, 128, 1), (TILE128, 515, 1024, 1024, 64),
     (TILE256, 256, 256, 128, 16), (TILE256, 300, 528, 512, 33), (TILE256, 1030, 768, 256, 48),
     (TILE256, 17, 16, 384, 1),
+    # K that is not a multiple of the stage depth: the last stage is zero filled
+    (TILE128, 129, 272, 800, 17), (TILE256, 300, 528, 1056, 33), (TILE256X128, 300, 400, 96, 25), (TILE128, 17, 768, 32, 48),
+    (TILE256, 70, 64, 4000, 4),
     (TILE256X128, 256, 128, 128, 8), (TILE256X128, 300, 400, 512, 25), (TILE256X128, 1030, 272, 256, 17),
     (TILE256X128, 17, 16, 384, 1), (TILE256X128, 512, 1024, 1024, 64),
     (SKINNY, 1, 64, 256, 4), (SKINNY, 3, 128, 768, 8), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
@@ -124,7 +127,7 @@ def test_largest_k_fills_the_accumulator(zq, orc):
     """K at the largest accepted values with every product at +-127*127: the INT32 accumulator ends
     within 0.01 % of its range and must not wrap in any schedule."""
     M, N, g = 3, 32, 2
-    for K, variants in ((133136, (SIMPLE,)),                                  # largest K the ABI takes (K % 16 == 0)
+    for K, variants in ((133136, (SIMPLE, TILE128, TILE256, TILE256X128)),    # largest K the ABI takes (K % 16 == 0)
                         (133120, (SIMPLE, TILE128, TILE256, TILE256X128, SKINNY, SKINNY_SPLITK))):
         xq = np.full((M, K), 127, np.int8)
         xq[1] = -127
