@@ -96,7 +96,7 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
             gemm_variant_workspace(kGemmSkinnySplitK, M, N, K, w_bits) > 0)
             return kGemmSkinnySplitK;
         if (gemm_variant_supports(kGemmSkinny, M, N, K, w_bits, 0)) return kGemmSkinny;
-        if (M <= 64) return kGemmSimple;
+        // K not a multiple of 256: the tiled schedules below take it
     }
     // Tiny problems (a BERT-base layer at 128 tokens) are all latency: one wave per 16x16 tile straight
     // from global memory starts and finishes sooner than a handful of LDS-tiled workgroups (6.2 vs 6.8 us).

@@ -159,7 +159,8 @@ def test_requant_epilogue(zq, orc):
 
 def test_dispatch_and_determinism(zq, orc):
     rng = zq_inputs.rng_for(4, 78)
-    for (M, N, K, g) in [(128, 768, 768, 48), (8, 2048, 2048, 128), (200, 512, 144, 32)]:
+    for (M, N, K, g) in [(128, 768, 768, 48), (8, 2048, 2048, 128), (200, 512, 144, 32), (64, 8192, 784, 64),
+                         (100, 4096, 2048, 64)]:
         xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
         nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
         ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
