@@ -453,7 +453,7 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
 }
 
-// FP16 activations x INT8 weights on the tiled schedules (K % 64 == 0).  The argument block is the
+// FP16 activations x INT8 weights on the tiled schedules.  The argument block is the
 // INT8 one with xq pointing at the FP16 activations and no token scales.
 hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
     GemmArgs a;

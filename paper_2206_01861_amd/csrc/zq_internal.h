@@ -39,10 +39,10 @@ hipError_t launch_weight_quant(const void *w, int N, int K, int groups, int bits
 // GeMM schedules.  The order is part of the test/tuning hook of the C ABI.
 enum GemmVariant {
     kGemmSimple = 0,      // one wave per 16x16 tile, operands from global; any legal shape
-    kGemmTile128 = 1,     // 128x128 block tile, four waves
+    kGemmTile128 = 1,     // 128x128 block tile, eight or four waves by tile count
     kGemmTile256 = 2,     // 256x256 block tile, eight waves
-    kGemmSkinny = 3,      // M <= 64: weight streaming, whole K in one workgroup
-    kGemmSkinnySplitK = 4,// M <= 64: K also split across workgroups (needs workspace)
+    kGemmSkinny = 3,      // M <= 128, K % 256 == 0: weight streaming, whole K in one workgroup
+    kGemmSkinnySplitK = 4,// same, K also split across workgroups (needs workspace)
     kGemmTile256x128 = 5, // 256x128 block tile, four waves, two workgroups per CU
     kGemmVariantCount = 6
 };
@@ -80,7 +80,7 @@ struct A16Args {
 };
 hipError_t launch_gemm_a16_simple(const A16Args &a, hipStream_t st);
 hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st);   // M <= 64, K % 256 == 0
-hipError_t launch_gemm_a16_tile(const A16Args &a, hipStream_t st);                       // K % 64 == 0
+hipError_t launch_gemm_a16_tile(const A16Args &a, hipStream_t st);                       // any K the ABI accepts
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);
