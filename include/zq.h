@@ -176,9 +176,23 @@ zq_status zq_dequantize_acc(const int32_t *acc, const float *s_tok, const float 
  * of the pre-activation.  The INT32 accumulator is not exported.
  *   xq, s_tok, s_w, groups, bias_fp16, M, N, K, workspace: as zq_gemm_i8_dequant
  *   wq        w_bits = 8: int8 [N,K];  w_bits = 4: packed uint8 [N,K/2]   (device)
- *   g_fp16    out, fp16 [M,N]: the activated tensor (device, required)
+ *   g_fp16    out, fp16 [M,N]: the activated tensor (device); may be NULL
+ *             when zq_gemm_quantizes_in_kernel() says 1 for the shape (the
+ *             tensor is then never written), otherwise ZQ_ERR_UNSUPPORTED
  *   gq_out    out, int8 [M,N];  s_tok_out  out, fp32 [M]                  (device, required)
  * N <= 32768 (a row of g is quantized from registers).  Errors as the GeMM calls.
+ *
+ * Where the quantization happens.  On the tiled schedules (large token counts)
+ * the GeMM kernel itself quantizes: the tiles that share a band of token rows
+ * exchange their row maxima through device memory owned by the library, wait
+ * for each other, and write the codes from their accumulator registers, so g
+ * is not read back (and not written at all when g_fp16 is NULL).  The same
+ * holds for out_q / out_s_tok of zq_gemm_i8_dequant and zq_gemm_w4a8_dequant.
+ * Elsewhere a second kernel quantizes the FP16 rows just written.  Both ways
+ * give the same bits.  Calls that quantize in the kernel must not overlap on
+ * one device (they share the exchange memory).  It needs N <= 16384 and
+ * (M rounded up to 256) * ceil(N / 256) <= 2^20; beyond that the second
+ * kernel is used.
  */
 zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, const void *wq, int w_bits,
                                        const float *s_w, int groups, const void *bias_fp16, int approx_tanh, int M,
@@ -215,6 +229,22 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
  * Process-wide; not for concurrent use.  Returns the previous value.
  */
 int zq_debug_force_gemm_variant(int variant);
+
+/*
+ * 1 if a GeMM call with out_q / gq_out on this shape quantizes its output
+ * inside the GeMM kernel (see zq_gemm_gelu_quant_tokenwise), else 0.
+ *
+ * zq_debug_set_in_kernel_quant: test and ablation hook; on = 0 makes every
+ * call use the second kernel.  Process-wide; returns the previous value.
+ *
+ * zq_quant_wait_expired: the wait of a tile for the rest of its band is
+ * bounded (about a second); *count_out receives the number of threads whose wait
+ * ran out since the last call of this function, 0 in every correct run (their
+ * rows would be wrong).  Synchronises the device.  ZQ_ERR_NULL, ZQ_ERR_HIP.
+ */
+int zq_gemm_quantizes_in_kernel(int M, int N, int K, int w_bits, size_t workspace_bytes);
+int zq_debug_set_in_kernel_quant(int on);
+zq_status zq_quant_wait_expired(int *count_out);
 
 /* Name of schedule `variant` (NULL when out of range), and the schedule the
  * dispatcher would choose for a shape. */

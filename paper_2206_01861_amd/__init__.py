@@ -7,6 +7,9 @@ stream.  There is no CPU fallback: a missing library is an error.
 from .binding import (  # noqa: F401
     ZQError,
     gemm_choose_variant,
+    gemm_quantizes_in_kernel,
+    quant_wait_expired,
+    set_in_kernel_quant,
     gemm_stream_plan,
     gemm_variant_name,
     gemm_workspace_bytes,

@@ -18,6 +18,7 @@ SYMBOLS = [
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
     "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_gelu_quant_tokenwise", "zq_quantize_tokenwise", "zq_dequantize_acc",
     "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant",
+    "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
 ]
 
 
@@ -72,6 +73,12 @@ def lib():
     L.zq_tune_clear.argtypes = []
     L.zq_tune_count.restype = ci
     L.zq_tune_count.argtypes = []
+    L.zq_gemm_quantizes_in_kernel.restype = ci
+    L.zq_gemm_quantizes_in_kernel.argtypes = [ci, ci, ci, ci, sz]
+    L.zq_debug_set_in_kernel_quant.restype = ci
+    L.zq_debug_set_in_kernel_quant.argtypes = [ci]
+    L.zq_quant_wait_expired.restype = ci
+    L.zq_quant_wait_expired.argtypes = [ctypes.POINTER(ci)]
     L.zq_debug_force_gemm_variant.restype = ci
     L.zq_debug_force_gemm_variant.argtypes = [ci]
     L.zq_gemm_variant_name.restype = ctypes.c_char_p
@@ -123,6 +130,23 @@ def gemm_variant_name(variant):
 
 def gemm_choose_variant(M, N, K, w_bits=8, workspace_bytes=0):
     return lib().zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes)
+
+
+def gemm_quantizes_in_kernel(M, N, K, w_bits=8, workspace_bytes=0):
+    """True if a GeMM call with quantized output on this shape quantizes inside the GeMM kernel."""
+    return bool(lib().zq_gemm_quantizes_in_kernel(M, N, K, w_bits, workspace_bytes))
+
+
+def set_in_kernel_quant(on):
+    """Test/ablation hook (zq_debug_set_in_kernel_quant); returns the previous setting."""
+    return bool(lib().zq_debug_set_in_kernel_quant(1 if on else 0))
+
+
+def quant_wait_expired():
+    """Workgroups whose bounded wait ran out since the last call (0 in a correct run); synchronises."""
+    c = ctypes.c_int(0)
+    _check(lib().zq_quant_wait_expired(ctypes.byref(c)))
+    return c.value
 
 
 def tune_set(m_lo, m_hi, N, K, w_bits, variant, row_blocks=0, k_splits=0):
@@ -239,11 +263,13 @@ def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, re
                  workspace, out, acc_out)
 
 
-def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh=False, workspace=None, out=None):
+def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh=False, workspace=None, out=None,
+                                 keep_g=True):
     """GeMM with bias + GeLU in its epilogue, then token-wise INT8 quantization of the FP16 result.
 
     wq int8 [N,K] or INT4-packed uint8 [N,K/2].  -> (g fp16 [M,N], gq int8 [M,N], s_tok fp32 [M]);
-    `out` = (g, gq, s) reuses caller tensors.
+    `out` = (g, gq, s) reuses caller tensors.  keep_g=False passes no g buffer (g comes back None):
+    allowed where gemm_quantizes_in_kernel() holds, an error elsewhere.
     """
     _dev(xq, torch.int8, "xq")
     _dev(s_tok, torch.float32, "s_tok")
@@ -263,9 +289,11 @@ def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh
     N = wq.shape[0]
     dev = xq.device
     g, gq, s = out if out is not None else (
-        torch.empty((M, N), dtype=torch.float16, device=dev),
+        torch.empty((M, N), dtype=torch.float16, device=dev) if keep_g else None,
         torch.empty((M, N), dtype=torch.int8, device=dev),
         torch.empty(M, dtype=torch.float32, device=dev))
+    if not keep_g:
+        g = None
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().zq_gemm_gelu_quant_tokenwise(_ptr(xq), _ptr(s_tok), _ptr(wq), w_bits, _ptr(s_w), int(s_w.numel()),
                                               _ptr(bias_fp16), 1 if approx_tanh else 0, M, N, K, _ptr(g), _ptr(gq),

@@ -8,6 +8,11 @@
 namespace {
 
 std::atomic<int> g_forced_variant{-1};
+std::atomic<int> g_in_kernel_quant{1};
+
+inline bool is_tile_variant(int v) {
+    return v == zq::kGemmTile128 || v == zq::kGemmTile256 || v == zq::kGemmTile256x128;
+}
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -28,8 +33,9 @@ zq_status check_rowquant(const void *in, const void *p0, const void *p1, int M, 
 zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, const float *s_w, int groups,
                       const void *bias, int M, int N, int K, void *out, int32_t *acc_out, int8_t *out_q,
                       float *out_s_tok, void *workspace, size_t workspace_bytes, int w_bits, int act,
-                      zq_stream stream) {
-    if (xq == nullptr || s_tok == nullptr || wq == nullptr || s_w == nullptr || out == nullptr) return ZQ_ERR_NULL;
+                      bool out_optional, zq_stream stream) {
+    if (xq == nullptr || s_tok == nullptr || wq == nullptr || s_w == nullptr) return ZQ_ERR_NULL;
+    if (out == nullptr && !(out_optional && out_q != nullptr)) return ZQ_ERR_NULL;
     if ((out_q == nullptr) != (out_s_tok == nullptr)) return ZQ_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
     if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
@@ -49,11 +55,19 @@ zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, cons
     } else {
         variant = zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes);
     }
+    // On the tiled schedules the output rows are quantized inside the GeMM kernel.
+    const bool in_kernel = out_q != nullptr && g_in_kernel_quant.load() != 0 && is_tile_variant(variant) &&
+                           zq::gemm_tile_quant_supported(M, N);
+    if (out == nullptr && !in_kernel) return ZQ_ERR_UNSUPPORTED;
     zq::GemmArgs a;
     a.xq = xq; a.s_tok = s_tok; a.wq = wq; a.s_w = s_w; a.groups = groups; a.bias = bias;
     a.M = M; a.N = N; a.K = K; a.out = out; a.acc_out = acc_out;
     a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.w_bits = w_bits; a.act = act;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (in_kernel) {
+        a.q_out = out_q; a.q_scale_out = out_s_tok;
+        return zq::launch_gemm_tile_quant(a, st) == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+    }
     if (zq::launch_gemm(variant, a, st) != hipSuccess) return ZQ_ERR_HIP;
     if (out_q != nullptr) {
         // Re-quantization for the next GeMM: token-wise quantizer over the FP16 row just written.
@@ -153,7 +167,7 @@ zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t 
                              int8_t *out_q, float *out_s_tok, void *workspace, size_t workspace_bytes,
                              zq_stream stream) {
     return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
-                       workspace, workspace_bytes, 8, 0, stream);
+                       workspace, workspace_bytes, 8, 0, false, stream);
 }
 
 zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8_t *wq4, const float *s_w,
@@ -161,7 +175,7 @@ zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8
                                int32_t *acc_out, int8_t *out_q, float *out_s_tok, void *workspace,
                                size_t workspace_bytes, zq_stream stream) {
     return gemm_common(xq, s_tok, wq4, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok,
-                       workspace, workspace_bytes, 4, 0, stream);
+                       workspace, workspace_bytes, 4, 0, false, stream);
 }
 
 zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, const void *wq, int w_bits,
@@ -172,7 +186,7 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
     if (approx_tanh != 0 && approx_tanh != 1) return ZQ_ERR_UNSUPPORTED;
     if (gq_out == nullptr || s_tok_out == nullptr) return ZQ_ERR_NULL;
     return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, g_fp16, nullptr, gq_out, s_tok_out, workspace,
-                       workspace_bytes, w_bits, approx_tanh ? 2 : 1, stream);
+                       workspace_bytes, w_bits, approx_tanh ? 2 : 1, true, stream);
 }
 
 zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
@@ -207,6 +221,23 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
 int zq_debug_force_gemm_variant(int variant) {
     if (variant >= zq::kGemmVariantCount) variant = -1;
     return g_forced_variant.exchange(variant < 0 ? -1 : variant);
+}
+
+int zq_debug_set_in_kernel_quant(int on) { return g_in_kernel_quant.exchange(on != 0 ? 1 : 0); }
+
+int zq_gemm_quantizes_in_kernel(int M, int N, int K, int w_bits, size_t workspace_bytes) {
+    if (M <= 0 || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return 0;
+    int variant = g_forced_variant.load();
+    if (variant < 0) variant = zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes);
+    return (g_in_kernel_quant.load() != 0 && is_tile_variant(variant) && zq::gemm_tile_quant_supported(M, N)) ? 1 : 0;
+}
+
+zq_status zq_quant_wait_expired(int *count_out) {
+    if (count_out == nullptr) return ZQ_ERR_NULL;
+    unsigned c = 0;
+    if (zq::quant_wait_expired(&c) != hipSuccess) return ZQ_ERR_HIP;
+    *count_out = (int)c;
+    return ZQ_OK;
 }
 
 const char *zq_gemm_variant_name(int variant) {

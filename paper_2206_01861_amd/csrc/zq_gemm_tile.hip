@@ -55,6 +55,19 @@ __device__ __forceinline__ void unpack8_nat(uint32_t p, uint32_t &d0, uint32_t &
     d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);   // lo2 hi2 lo3 hi3
 }
 
+// State of the in-kernel output quantization (QOUT = 1).  The tiles that share a band of token
+// rows publish the row maxima of their tile in g_row_max_slots, one 8-byte slot per (tile, row):
+// the float bits of max |g| below, the launch generation above.  A slot counts only if it carries
+// the generation of the running launch, so nothing is ever cleared; the last workgroup of a launch
+// to finish reading moves the generation on (the device does it, so replaying a captured launch
+// works).  Calls that quantize in the kernel must not overlap on one device: they share this state.
+constexpr int kMaxQuantSlots = 1 << 20;
+constexpr unsigned kQuantSpinLimit = 1u << 20;        // polls of ~1 us: about a second, far beyond any launch
+__device__ unsigned long long g_row_max_slots[kMaxQuantSlots];
+__device__ unsigned int g_quant_generation = 1;       // never 0: untouched slots read as generation 0
+__device__ unsigned int g_quant_done;                 // workgroups of the running launch that have read their band
+__device__ unsigned int g_quant_wait_expired;         // number of threads whose wait ran out
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE>
 struct TileCfg {
     static constexpr int kWaves = WAVES_M * WAVES_N;
@@ -65,16 +78,19 @@ struct TileCfg {
     static constexpr int kEpi = kWaves * 32 * kEpiRow;
     static constexpr int kMain = NSTAGE * kStage > kEpi ? NSTAGE * kStage : kEpi;
     static constexpr int kLds = kMain + (2 * BN + BM) * 4;    // + column scale, column bias, row scale
+    static constexpr int kLdsQ = kLds + (WAVES_N + 1) * BM * 4;   // + per-wave row maxima, row 1/scale
+    static_assert(BM * BN <= kMain, "the INT8 code tile reuses the stage ring");
 };
 
 }  // namespace
 
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
-    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act) {
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act,
+    int8_t *__restrict__ q_out, float *__restrict__ q_scale_out) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -95,6 +111,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr bool STAGED_W = (WBITS == 4) || (XT == 1);
     constexpr int XB = (XT == 1) ? 2 : 1;            // bytes per activation value
     static_assert(XT == 0 || WBITS == 8, "FP16 activations go with INT8 weights");
+    static_assert(QOUT == 0 || XT == 0, "the output quantization is built for the INT8 product");
     constexpr int DIRECT_UNITS = STAGED_W ? XU : (XU + WU);
     static_assert(XU % NW == 0 && WU % NW == 0, "load units must split evenly over the waves");
     using AccT = typename std::conditional<XT == 1, float32x16, int32x16>::type;
@@ -108,17 +125,27 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
 
     // ---- tile coordinates, XCD aware --------------------------------------
-    const int nb = tiles_m * tiles_n;
-    const int b = blockIdx.x;
-    const int xcd = b % 8;
-    const int per = nb / 8, rem = nb % 8;
-    const int t = xcd * per + (xcd < rem ? xcd : rem) + b / 8;   // XCD x owns a contiguous run of logical tiles
-    constexpr int GM = 8;                                        // tile rows per band
-    const int band = t / (GM * tiles_n);
-    const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
-    const int within = t - band * GM * tiles_n;
-    const int tm = band * GM + within % band_rows;
-    const int tn = within / band_rows;
+    // QOUT: the tiles of one band of token rows have consecutive ids.  A tile waits for the others of
+    // its band in the epilogue, and workgroups start in id order on every XCD, so the oldest
+    // unfinished band always has all its tiles running.  (Round-robin over the XCDs still gives each
+    // XCD a fixed set of weight column tiles.)
+    int tm, tn;
+    if constexpr (QOUT == 1) {
+        tm = blockIdx.x / tiles_n;
+        tn = blockIdx.x % tiles_n;
+    } else {
+        const int nb = tiles_m * tiles_n;
+        const int b = blockIdx.x;
+        const int xcd = b % 8;
+        const int per = nb / 8, rem = nb % 8;
+        const int t = xcd * per + (xcd < rem ? xcd : rem) + b / 8;   // XCD x owns a contiguous run of logical tiles
+        constexpr int GM = 8;                                        // tile rows per band
+        const int band = t / (GM * tiles_n);
+        const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
+        const int within = t - band * GM * tiles_n;
+        tm = band * GM + within % band_rows;
+        tn = within / band_rows;
+    }
     const int m0 = tm * BM;
     const int n0 = tn * BN;
 
@@ -356,8 +383,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     const int nw = n0 + wn * WN;              // first output column of this wave
     constexpr int LPR = WN * 2 / 16;          // lanes per output row (16 bytes each)
     constexpr int RPI = 64 / LPR;             // rows per store instruction
+    float rmax[FM];                           // QOUT: max |g| of this lane's token rows
+    unsigned gen = 0;                         // QOUT: generation of this launch, back before it is needed
+    if constexpr (QOUT == 1)
+        gen = __hip_atomic_load(&g_quant_generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
+        rmax[fm] = 0.0f;
         const float st = row_scale[wm * WM + fm * 32 + lr];
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) {
@@ -390,23 +422,136 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 half4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
-                *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
+                if (QOUT == 0 || out != nullptr) *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
                 if (XT == 0 && acc_out != nullptr) {
                     const int m = mw + fm * 32 + lr;
                     if (m < M && nw + nl < N) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
+                }
+                if constexpr (QOUT == 1) {
+                    // the accumulator registers now hold the output as rounded to FP16: the codes
+                    // below are those of the stored tensor
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = (float)o[e];
+                        acc[fn][fm][4 * q + e] = __float_as_int(g);
+                        rmax[fm] = fmaxf(rmax[fm], fabsf(g));
+                    }
                 }
             }
         }
         // The wave reads back its own 32 rows (LDS operations of one wave complete in order) and
         // stores whole row segments.
+        if (QOUT == 0 || out != nullptr) {
 #pragma unroll
-        for (int i = 0; i < 32 / RPI; ++i) {
-            const int row = i * RPI + lane / LPR;
-            const int col = (lane % LPR) * 8;
-            const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
-            const int m = mw + fm * 32 + row;
-            const int n = nw + col;
-            if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int row = i * RPI + lane / LPR;
+                const int col = (lane % LPR) * 8;
+                const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
+                const int m = mw + fm * 32 + row;
+                const int n = nw + col;
+                if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+            }
+        }
+    }
+
+    if constexpr (QOUT == 1) {
+        // ---- token-wise quantization of the output rows from registers (App. A.2) ----
+        // A row of g spans the tiles_n tiles of this band.  Row maxima: lane pair -> the waves along
+        // N (LDS) -> the band (slots in device memory).  Columns past N repeat column N-1 and rows
+        // past M repeat row M-1 (clamped loads), so they never raise a maximum.
+        float *wave_max = row_scale + BM;              // [WAVES_N][BM]
+        float *row_inv = wave_max + WAVES_N * BM;      // [BM]
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+            rmax[fm] = fmaxf(rmax[fm], __shfl_xor(rmax[fm], 32));
+            if (lc == 0) wave_max[wn * BM + wm * WM + fm * 32 + lr] = rmax[fm];
+        }
+        __syncthreads();
+        if (tid < BM) {
+            float a = wave_max[tid];
+#pragma unroll
+            for (int w = 1; w < WAVES_N; ++w) a = fmaxf(a, wave_max[w * BM + tid]);
+            // Publish this tile's maxima, then collect the band's: one store and, when the other
+            // tiles are already there, one round of loads.  The wait is bounded: a thread whose wait
+            // ran out goes on with what it has and counts itself in g_quant_wait_expired.
+            unsigned long long *band = g_row_max_slots + (size_t)tm * tiles_n * BM + tid;
+            __hip_atomic_store(band + (size_t)tn * BM, ((unsigned long long)gen << 32) | __float_as_uint(a),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            constexpr int QB = 16;                     // slots fetched per round
+            unsigned spins = 0;
+            for (int j0 = 0; j0 < tiles_n; j0 += QB) {
+                while (true) {
+                    unsigned long long v[QB];
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        const int j = (j0 + u < tiles_n) ? j0 + u : tiles_n - 1;
+                        v[u] = __hip_atomic_load(band + (size_t)j * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    bool all = true;
+                    float mx = a;
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        all = all && (unsigned)(v[u] >> 32) == gen;
+                        mx = fmaxf(mx, __uint_as_float((unsigned)v[u]));
+                    }
+                    if (all) {
+                        a = mx;
+                        break;
+                    }
+                    if (++spins > kQuantSpinLimit) {
+                        __hip_atomic_fetch_add(&g_quant_wait_expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            float scale, inv;
+            quant_scales(a, 127.0f, scale, inv);
+            row_inv[tid] = inv;
+            if (tn == 0 && m0 + tid < M) q_scale_out[m0 + tid] = scale;
+        }
+        __syncthreads();
+        // This workgroup has read its band.  The count comes back while the codes are written; the
+        // workgroup that completes it ends the launch's generation (below).
+        unsigned done_before = 0;
+        if (tid == 0)
+            done_before = __hip_atomic_fetch_add(&g_quant_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Codes: four consecutive columns per lane -> one dword of the BM x BN code tile in LDS (the
+        // stage ring is free now), 16-byte chunks XOR-swizzled by row so that the 32 rows of a
+        // fragment hit different banks; then every row leaves as one contiguous segment.
+        constexpr int QCH = BN / 16;                   // 16-byte chunks per row of the code tile
+        uint8_t *ct = smem;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+            const int row = wm * WM + fm * 32 + lr;
+            const float inv = row_inv[row];
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = wn * WN + fn * 32 + 8 * q + 4 * lc;
+                    const uint32_t d = pack4_code_bits(
+                        quant_code_bits(__int_as_float(acc[fn][fm][4 * q]), inv),
+                        quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 1]), inv),
+                        quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 2]), inv),
+                        quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 3]), inv));
+                    *reinterpret_cast<uint32_t *>(ct + row * BN + (((col / 16) ^ (row & (QCH - 1))) * 16) + col % 16) = d;
+                }
+            }
+        }
+        __syncthreads();
+        for (int idx = tid; idx < BM * QCH; idx += NT) {
+            const int row = idx / QCH, c = idx % QCH;
+            const int32x4 v = *reinterpret_cast<const int32x4 *>(ct + row * BN + ((c ^ (row & (QCH - 1))) * 16));
+            const int m = m0 + row, n = n0 + c * 16;
+            if (m < M && n < N) *reinterpret_cast<int32x4 *>(q_out + (size_t)m * N + n) = v;
+        }
+        if (tid == 0 && done_before == gridDim.x - 1u) {
+            __hip_atomic_store(&g_quant_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned next = gen + 1u;
+            __hip_atomic_store(&g_quant_generation, next != 0u ? next : 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 #endif
@@ -414,19 +559,29 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 
 namespace {
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0>
 hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st) {
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
-    constexpr size_t lds = Cfg::kLds;
+    constexpr size_t lds = QOUT ? Cfg::kLdsQ : Cfg::kLds;
     static std::atomic<uint64_t> configured{0};
-    const void *kernel = reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT>);
+    const void *kernel =
+        reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT>), dim3(tiles_m * tiles_n),
-                       dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq), a.s_w,
-                       a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                       reinterpret_cast<half_t *>(a.out), a.acc_out, tiles_m, tiles_n, a.act);
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT>),
+                       dim3(tiles_m * tiles_n), dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok,
+                       reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
+                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
+                       a.acc_out, tiles_m, tiles_n, a.act, a.q_out, a.q_scale_out);
     return hipGetLastError();
+}
+
+// Tile edge of the schedule that quantizes its output in the kernel: 256 where the plain call
+// would use it or where 128x128 tiles would outnumber what eight-wave workgroups hold at once.
+int quant_tile_edge(int M, int N) {
+    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    return (t256 >= 160 || t128 > 384) ? 256 : 128;
 }
 
 }  // namespace
@@ -451,6 +606,35 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     }
     if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 64, 4, 8>(a, st);
     return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
+}
+
+// The tiled GeMM with the token-wise quantization of its output inside the kernel (a.q_out,
+// a.q_scale_out; a.out optional).  The tiles of a band of token rows wait for each other, so a band
+// must fit on the chip several times over, and every (tile, row) needs a slot of the exchange array.
+bool gemm_tile_quant_supported(int M, int N) {
+    const int edge = quant_tile_edge(M, N);
+    const int tiles_m = (M + edge - 1) / edge, tiles_n = (N + edge - 1) / edge;
+    return tiles_n <= 64 && (long)tiles_m * tiles_n * edge <= kMaxQuantSlots;
+}
+
+hipError_t launch_gemm_tile_quant(const GemmArgs &a, hipStream_t st) {
+    if (!gemm_tile_quant_supported(a.M, a.N) || a.q_out == nullptr || a.q_scale_out == nullptr)
+        return hipErrorInvalidValue;
+    if (quant_tile_edge(a.M, a.N) == 256) {
+        if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 0, 1>(a, st);
+        return launch_tile_t<256, 256, 2, 4, 128, 2, 4, 0, 1>(a, st);
+    }
+    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 4, 128, 4, 8, 0, 1>(a, st);
+    return launch_tile_t<128, 128, 2, 4, 128, 4, 4, 0, 1>(a, st);
+}
+
+// Number of workgroups whose bounded wait for their band ran out since the last call (0 in any
+// correct run); synchronises the device.
+hipError_t quant_wait_expired(unsigned *count) {
+    unsigned zero = 0;
+    hipError_t e = hipMemcpyFromSymbol(count, HIP_SYMBOL(g_quant_wait_expired), sizeof(unsigned));
+    if (e != hipSuccess) return e;
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_quant_wait_expired), &zero, sizeof(unsigned));
 }
 
 // FP16 activations x INT8 weights on the tiled schedules.  The argument block is the

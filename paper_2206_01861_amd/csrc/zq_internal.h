@@ -61,7 +61,14 @@ struct GemmArgs {
     size_t workspace_bytes;
     int w_bits;           // 8 or 4
     int act;              // activation applied to acc*scale+bias before the FP16 rounding: 0 none, 1 GeLU erf, 2 GeLU tanh
+    int8_t *q_out = nullptr;       // launch_gemm_tile_quant: int8 [M,N] codes of the output rows
+    float *q_scale_out = nullptr;  //                         fp32 [M] their scales
 };
+
+// Tiled GeMM that also quantizes its output rows token-wise inside the kernel (out may be null).
+bool gemm_tile_quant_supported(int M, int N);
+hipError_t launch_gemm_tile_quant(const GemmArgs &a, hipStream_t st);
+hipError_t quant_wait_expired(unsigned *count);
 
 // A caller-supplied cut of the streaming schedules for this shape, if one was registered.
 bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_splits);

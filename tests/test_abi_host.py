@@ -146,11 +146,32 @@ def test_gemm_gelu_quant_validation():
     assert call(tanh=2) == E_UNSUP
     assert call(gq=None) == E_NULL
     assert call(s=None) == E_NULL
-    assert call(g=None) == E_NULL                  # the activated FP16 tensor is the quantizer's input
+    # eight tokens run on a streaming schedule, whose output a second kernel quantizes: that kernel
+    # reads the FP16 tensor, so the call is refused without it (nothing is launched)
+    assert zq.lib().zq_gemm_quantizes_in_kernel(8, 64, 128, 8, 0) == 0
+    assert call(g=None) == E_UNSUP
     assert call(wq=None) == E_NULL
     assert call(N=32768 + 64, groups=4) == E_SHAPE # a row of g must fit the quantizer's registers
     assert call(K=48, w_bits=4) == E_SHAPE
     assert call(g=P + 8) == E_ALIGN
+
+
+def test_where_the_output_is_quantized():
+    """Tiled schedules quantize in the GeMM kernel, within the limits of the exchange arrays and of
+    the band that must be resident at once; the debug switch turns it off."""
+    q = zq.gemm_quantizes_in_kernel
+    assert q(4096, 4096, 1024, 8) and q(4096, 4096, 1024, 4) and q(16384, 6144, 24576, 8)
+    assert q(65536, 4096, 64, 8) and not q(65537, 4096, 64, 8)            # slots of the exchange array
+    assert q(4096, 16384, 4096, 8) and not q(4096, 16384 + 256, 4096, 8)  # tiles per band
+    assert not q(64, 4096, 4096, 8) and not q(1, 16, 16, 8)               # streaming / untiled schedules
+    assert not q(0, 16, 16, 8) and not q(16, 16, 16, 5)
+    prev = zq.set_in_kernel_quant(False)
+    try:
+        assert prev is True and not q(4096, 4096, 1024, 8)
+    finally:
+        assert zq.set_in_kernel_quant(prev) is False
+    assert q(4096, 4096, 1024, 8)
+    assert zq.lib().zq_quant_wait_expired(None) == E_NULL
 
 
 def test_standalone_quantizer_and_dequantizer_validation():

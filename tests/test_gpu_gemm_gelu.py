@@ -81,3 +81,79 @@ def test_fused_chain_tracks_two_call_chain(zq, orc):
     assert rel_s.max() < 2e-3
     diff = np.abs(host(gq).astype(np.int32) - host(hq).astype(np.int32))
     assert diff.max() <= 1 and (diff != 0).mean() < 0.05
+
+
+# (M, N, K, groups): both tile edges of the schedule that quantizes inside the GeMM kernel, ragged
+# in M and N, bands of 2 to 40 tiles, one tile per band, K down to a single stage.
+IN_KERNEL = [
+    (300, 400, 384, 25), (129, 144, 64, 9), (515, 1024, 1024, 64), (1000, 2064, 256, 129),
+    (2100, 5008, 128, 313), (4096, 4096, 1024, 64), (130, 8192, 128, 512), (5000, 272, 96, 17),
+    (3000, 6160, 64, 385),      # more tiles than compute units: later bands start as earlier ones leave
+]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,N,K,g", IN_KERNEL)
+def test_in_kernel_quantization_equals_second_kernel(zq, orc, M, N, K, g, bits):
+    """The GeMM kernel that quantizes its own output rows (row maxima exchanged between the tiles of
+    a band) gives the bits of the two-kernel path: FP16 tensor, codes and scales; with and without
+    the FP16 tensor; twice in a row (the exchange state must be back at zero); and for the plain
+    GeMM's out_q.  Sampled rows are also checked against the oracle."""
+    print("in-kernel quant", bits, M, N, K, g, flush=True)
+    if bits == 4 and K % 32:
+        pytest.skip("INT4 needs K % 32 == 0")
+    rng = zq_inputs.rng_for(7, M + N + K + bits)
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
+    s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
+    args = (dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias))
+    gemm = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
+    # small problems go to the untiled schedule by themselves: put them on a tiled one
+    tiled = zq.gemm_choose_variant(M, N, K, bits) in (TILE128, TILE256)
+    prev_variant = zq.force_gemm_variant(-1 if tiled else TILE128)
+    try:
+        assert zq.gemm_quantizes_in_kernel(M, N, K, bits)
+        prev = zq.set_in_kernel_quant(False)
+        try:
+            assert not zq.gemm_quantizes_in_kernel(M, N, K, bits)
+            g_ref, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)
+            o_ref, _, oq_ref, os_ref = gemm(*args, requant=True)
+            torch.cuda.synchronize()
+        finally:
+            zq.set_in_kernel_quant(prev)
+        runs = []
+        for rep in range(2):
+            g1, q1, s1 = zq.zq_gemm_gelu_quant_tokenwise(*args)
+            g2, q2, s2 = zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False)
+            o3, _, q3, s3 = gemm(*args, requant=True)
+            torch.cuda.synchronize()
+            runs.append((g1, q1, s1, g2, q2, s2, o3, q3, s3))
+    finally:
+        zq.force_gemm_variant(prev_variant)
+    for rep, (g1, q1, s1, g2, q2, s2, o3, q3, s3) in enumerate(runs):
+        assert g2 is None
+        assert_bit_equal(host(g1), host(g_ref), "g rep %d" % rep)
+        assert_bit_equal(host(s1), host(s_ref), "s_tok rep %d" % rep)
+        assert_bit_equal(host(q1), host(q_ref), "codes rep %d" % rep)
+        assert_bit_equal(host(s2), host(s_ref), "s_tok without g rep %d" % rep)
+        assert_bit_equal(host(q2), host(q_ref), "codes without g rep %d" % rep)
+        assert_bit_equal(host(o3), host(o_ref), "plain GeMM out rep %d" % rep)
+        assert_bit_equal(host(s3), host(os_ref), "plain GeMM out_s_tok rep %d" % rep)
+        assert_bit_equal(host(q3), host(oq_ref), "plain GeMM out_q rep %d" % rep)
+    assert zq.quant_wait_expired() == 0
+    rows = sorted(set([0, M - 1, M // 2, min(M - 1, 127), min(M - 1, 128), min(M - 1, 255), min(M - 1, 256)]))
+    _check_fused(orc, host(g1)[rows], host(q1)[rows], host(s1)[rows], xq[rows], s_tok[rows], codes, s_w, bias, False,
+                 "in-kernel %d-bit %dx%dx%d" % (bits, M, N, K))
+
+
+def test_missing_fp16_output_needs_the_in_kernel_path(zq):
+    """Without a buffer for g the call is only legal where the GeMM kernel quantizes; elsewhere it
+    is refused before anything is launched."""
+    M, N, K, g = 8, 256, 256, 16
+    assert not zq.gemm_quantizes_in_kernel(M, N, K, 8)
+    xq = torch.zeros((M, K), dtype=torch.int8, device="cuda")
+    wq = torch.zeros((N, K), dtype=torch.int8, device="cuda")
+    st = torch.ones(M, device="cuda")
+    sw = torch.ones(g, device="cuda")
+    with pytest.raises(zq.ZQError) as e:
+        zq.zq_gemm_gelu_quant_tokenwise(xq, st, wq, sw, keep_g=False)
+    assert e.value.code == 4
