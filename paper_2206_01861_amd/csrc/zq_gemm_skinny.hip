@@ -103,6 +103,30 @@ __device__ __forceinline__ void stream_load16(int32x4 &dst, int voff, uint32x4 s
                  : "v"(voff), "s"(srd), "s"(soff), "n"(IMM));
 }
 
+// Weight loads of a 16-row strip, 64 bytes of each row per load.  The vector cache works through a
+// load four lanes at a time and is fastest when those four lanes are contiguous in memory; in the
+// matrix-core operand layout (lane = row a of 16, 16-byte chunk b of 4: consecutive lanes are
+// consecutive rows) every group of four touches four lines, and that costs 12-15 % of the stream
+// once the activation tile shares the cache (64 tokens).  So the loads run chunk-fastest (lane =
+// 4a + b) and one cross-lane permutation per register turns the result into the operand layout.
+template <int LW>
+__device__ __forceinline__ void issue_strip(int32x4 (&dst)[LW], int voff, uint32x4 srd, int soff) {
+    stream_load16<0>(dst[0], voff, srd, soff);
+    stream_load16<64>(dst[1], voff, srd, soff);
+    if (LW == 4) {
+        stream_load16<128>(dst[2], voff, srd, soff);
+        stream_load16<192>(dst[3], voff, srd, soff);
+    }
+}
+// pull = 4 * (4 * (lane % 16) + lane / 16): byte address of the lane that holds (row lane%16, chunk lane/16).
+template <int LW>
+__device__ __forceinline__ void strip_operands(const int32x4 (&w)[LW], int32x4 (&t)[LW], int pull) {
+#pragma unroll
+    for (int i = 0; i < LW; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[i][e] = __builtin_amdgcn_ds_bpermute(pull, w[i][e]);
+}
+
 // One dword fetched the same way (used for the operands of the epilogue): issued here, not tracked
 // by the compiler, usable only after a wait followed by landed().
 __device__ __forceinline__ void async_load_dword(uint32_t &dst, const void *p) {
@@ -213,19 +237,15 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int wrow_bytes = (WBITS == 8) ? K : K / 2;
     const uint32x4 rs_w = make_srd(wq, (uint32_t)((size_t)N * wrow_bytes));
     constexpr int W_STAGE_BYTES = (WBITS == 8) ? kStageK : kStageK / 2;   // bytes of a row per stage
-    const int voff_w = (int)((uint32_t)(strip * 16 + r) * (uint32_t)wrow_bytes + (uint32_t)(j * 16));
+    const int voff_w = (int)((uint32_t)(strip * 16 + lane / 4) * (uint32_t)wrow_bytes + (uint32_t)((lane % 4) * 16));
+    const int pull = 4 * (4 * r + j);
 
     int32x4 wreg[DW][LW];
     // Stage i of this workgroup; indices past the end re-load the last stage (never computed).
     auto issue_w = [&](int i, int32x4(&dst)[LW]) __attribute__((always_inline)) {
         if (i > n - 1) i = n - 1;
         const int soff = __builtin_amdgcn_readfirstlane((k_lo + i) * W_STAGE_BYTES);   // wave-uniform by construction
-        stream_load16<0>(dst[0], voff_w, rs_w, soff);
-        stream_load16<64>(dst[1], voff_w, rs_w, soff);
-        if (LW == 4) {
-            stream_load16<128>(dst[2], voff_w, rs_w, soff);
-            stream_load16<192>(dst[3], voff_w, rs_w, soff);
-        }
+        issue_strip<LW>(dst, voff_w, rs_w, soff);
     };
 
     int32x4 acc[MT];
@@ -233,7 +253,9 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     for (int mt = 0; mt < MT; ++mt) acc[mt] = int32x4{0, 0, 0, 0};
 
     const int x_lane = r * kStageK;                   // this lane's row inside a 16-row block
-    auto compute = [&](const int32x4(&w)[LW], const uint8_t *xs) __attribute__((always_inline)) {
+    auto compute = [&](const int32x4(&wl)[LW], const uint8_t *xs) __attribute__((always_inline)) {
+        int32x4 w[LW];
+        strip_operands<LW>(wl, w, pull);
         if (WBITS == 8) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {             // k step i: bytes 64i + 16j of the stage
@@ -478,15 +500,13 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
 
     // ---- consumers: INT8 weight strip through registers ----------------------
     const uint32x4 rs_w = make_srd(wq, (uint32_t)((size_t)N * K));
-    const int voff_w = (int)((uint32_t)(strip * 16 + r) * (uint32_t)K + (uint32_t)(j * 16));
+    const int voff_w = (int)((uint32_t)(strip * 16 + lane / 4) * (uint32_t)K + (uint32_t)((lane % 4) * 16));
+    const int pull = 4 * (4 * r + j);
     int32x4 wreg[DW][LW];
     auto issue_w = [&](int i, int32x4(&dst)[LW]) __attribute__((always_inline)) {
         if (i > n - 1) i = n - 1;
         const int soff = __builtin_amdgcn_readfirstlane((k_lo + i) * kStageK);
-        stream_load16<0>(dst[0], voff_w, rs_w, soff);
-        stream_load16<64>(dst[1], voff_w, rs_w, soff);
-        stream_load16<128>(dst[2], voff_w, rs_w, soff);
-        stream_load16<192>(dst[3], voff_w, rs_w, soff);
+        issue_strip<LW>(dst, voff_w, rs_w, soff);
     };
 
     float32x4 acc[MT];
@@ -494,7 +514,9 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
     for (int mt = 0; mt < MT; ++mt) acc[mt] = float32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int x_lane = r * X_ROW;
-    auto compute = [&](const int32x4(&w)[LW], const uint8_t *xs) __attribute__((always_inline)) {
+    auto compute = [&](const int32x4(&wl)[LW], const uint8_t *xs) __attribute__((always_inline)) {
+        int32x4 w[LW];
+        strip_operands<LW>(wl, w, pull);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
