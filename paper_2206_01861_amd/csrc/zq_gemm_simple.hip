@@ -37,22 +37,53 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const int8_t *__restri
     const size_t wrow_bytes = (WBITS == 8) ? (size_t)K : (size_t)(K / 2);
     const uint8_t *wrow = wq + (size_t)(n0 + r) * wrow_bytes;
 
+    // The epilogue's operands first: their round trip then runs under the main loop.
+    const int m_ld = (m0 + r < M) ? m0 + r : M - 1;
+    const int n_ld = n0 + 4 * (lane / 16);
+    const float sc = s_tok[m_ld] * s_w[n_ld / gs];   // four consecutive columns never straddle a group (gs % 16 == 0)
+    half4 bv = {0, 0, 0, 0};
+    if (bias != nullptr) bv = *reinterpret_cast<const half4 *>(bias + n_ld);
+
+    auto load_step = [&](int k, int32x4 &a, int32x4 &b) __attribute__((always_inline)) {
+        b = *reinterpret_cast<const int32x4 *>(xrow + k);
+        if (WBITS == 8) {
+            a = *reinterpret_cast<const int32x4 *>(wrow + k);
+        } else {
+            const uint2 p = *reinterpret_cast<const uint2 *>(wrow + k / 2);
+            uint32_t w0, w1, w2, w3;
+            unpack8_plain(p.x, w0, w1);
+            unpack8_plain(p.y, w2, w3);
+            a = int32x4{(int)w0, (int)w1, (int)w2, (int)w3};
+        }
+    };
     int32x4 acc = {0, 0, 0, 0};
-    for (int k0 = 0; k0 < K; k0 += 64) {
+    // Whole groups of four 64-deep steps.  The eight loads of a group are issued together and the
+    // next group is requested before the current one is multiplied, so the loop costs about one
+    // memory round trip per two groups instead of one per step.
+    auto load_group = [&](int g, int32x4(&a)[4], int32x4(&b)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_step(g * 256 + 64 * u + kc, a[u], b[u]);
+    };
+    auto mfma_group = [&](const int32x4(&a)[4], const int32x4(&b)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u], b[u], acc, 0, 0, 0);
+    };
+    const int ng = K / 256;
+    int32x4 a0[4], b0[4], a1[4], b1[4];
+    if (ng > 0) load_group(0, a0, b0);
+    for (int g = 0; g < ng; g += 2) {
+        if (g + 1 < ng) load_group(g + 1, a1, b1);
+        mfma_group(a0, b0);
+        if (g + 1 < ng) {
+            if (g + 2 < ng) load_group(g + 2, a0, b0);
+            mfma_group(a1, b1);
+        }
+    }
+    int k0 = ng * 256;
+    for (; k0 < K; k0 += 64) {
         const int k = k0 + kc;
         int32x4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
-        if (k < K) {                           // K % 16 == 0, so a slice is all inside or all outside
-            b = *reinterpret_cast<const int32x4 *>(xrow + k);
-            if (WBITS == 8) {
-                a = *reinterpret_cast<const int32x4 *>(wrow + k);
-            } else {
-                const uint2 p = *reinterpret_cast<const uint2 *>(wrow + k / 2);
-                uint32_t w0, w1, w2, w3;
-                unpack8_plain(p.x, w0, w1);
-                unpack8_plain(p.y, w2, w3);
-                a = int32x4{(int)w0, (int)w1, (int)w2, (int)w3};
-            }
-        }
+        if (k < K) load_step(k, a, b);         // K % 16 == 0, so a slice is all inside or all outside
         acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc, 0, 0, 0);
     }
 
@@ -62,12 +93,11 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const int8_t *__restri
     const int m = m0 + r;
     if (m >= M) return;
     const int n = n0 + 4 * (lane / 16);
-    const float sc = s_tok[m] * s_w[n / gs];   // four consecutive columns never straddle a group (gs % 16 == 0)
     half4 o;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         float f = (float)acc[v] * sc;
-        if (bias != nullptr) f += (float)bias[n + v];
+        f += (float)bv[v];                    // zero without a bias
         o[v] = (half_t)apply_activation(f, act);
     }
     *reinterpret_cast<half4 *>(out + (size_t)m * N + n) = o;
