@@ -83,14 +83,21 @@ __device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
 __device__ __forceinline__ float gelu_erf(float u) {
     const float a = fabsf(u);
     const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, a, 1.0f));
-    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    // The leading coefficient lives in a register of its own (the asm has no inputs, so the
+    // compiler keeps one copy): the first Horner step is then one multiply-add with one literal
+    // instead of a move and a multiply-accumulate.
+    float c5;
+    asm("v_mov_b32 %0, 0x3f07dc22" : "=v"(c5));       // 0.5 * 1.061405429
+    float p = fmaf(t, c5, 0.5f * -1.453152027f);
     p = fmaf(t, p, 0.5f * 1.421413741f);
     p = fmaf(t, p, 0.5f * -0.284496736f);
     p = fmaf(t, p, 0.5f * 0.254829592f);
     const float w = u * 0.84932180028801904272f;      // sqrt(log2(e) / 2): exp(-u^2 / 2) = 2^(-w^2)
     const float e = __builtin_amdgcn_exp2f(-(w * w));
     const float h = (p * t) * e;
-    return fmaf(-a, h, __builtin_amdgcn_fmed3f(u, 0.0f, __builtin_inff()));   // max(u, 0) in one instruction
+    float pos;                                        // max(u, 0) in one instruction (no canonicalising copy)
+    asm("v_max_f32 %0, 0, %1" : "=v"(pos) : "v"(u));
+    return fmaf(-a, h, pos);
 }
 
 // GeLU, tanh form: 0.5 u (1 + tanh(v)) = u * (1 - 1 / (1 + exp(2v))).
@@ -123,6 +130,20 @@ __device__ __forceinline__ float apply_activation(float f, int act) {
     if (act == 1) return gelu_erf(f);
     if (act == 2) return gelu_tanh(f);
     return f;
+}
+
+// The same over N values at once.  The choice is made once, outside the loop over the values, so each
+// branch is straight-line code whose N dependency chains (one reciprocal and one exponential each)
+// the compiler can interleave; with the choice inside, every value ran its chain alone.
+template <int N>
+__device__ __forceinline__ void apply_activation_n(float (&f)[N], int act) {
+    if (act == 1) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) f[e] = gelu_erf(f[e]);
+    } else if (act == 2) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) f[e] = gelu_tanh(f[e]);
+    }
 }
 
 // Workgroup barrier for kernels that keep asynchronous global->LDS loads in flight across it.

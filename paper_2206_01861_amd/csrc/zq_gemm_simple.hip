@@ -93,13 +93,13 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const int8_t *__restri
     const int m = m0 + r;
     if (m >= M) return;
     const int n = n0 + 4 * (lane / 16);
+    float f[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) f[v] = (float)acc[v] * sc + (float)bv[v];   // bv is zero without a bias
+    apply_activation_n<4>(f, act);
     half4 o;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        float f = (float)acc[v] * sc;
-        f += (float)bv[v];                    // zero without a bias
-        o[v] = (half_t)apply_activation(f, act);
-    }
+    for (int v = 0; v < 4; ++v) o[v] = (half_t)f[v];
     *reinterpret_cast<half4 *>(out + (size_t)m * N + n) = o;
     if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n) = acc;
 }

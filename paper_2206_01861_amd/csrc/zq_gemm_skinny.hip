@@ -403,13 +403,16 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
         const int m = mt * 16 + r;
         if (m < M) {
             const float sc = __uint_as_float(st_bits[mt]) * sw;
-            half4 o;
+            float f[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float f = (float)acc[mt][e] * sc;
-                if (bias != nullptr) f += (float)bias4[e];
-                o[e] = (half_t)apply_activation(f, act);
+                f[e] = (float)acc[mt][e] * sc;
+                if (bias != nullptr) f[e] += (float)bias4[e];
             }
+            apply_activation_n<4>(f, act);
+            half4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
             *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
             if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n_col) = acc[mt];
         }

@@ -415,10 +415,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 }
                 float f[4] = {fv[0] * (st * sc.x) + cb.x, fv[1] * (st * sc.y) + cb.y,
                               fv[2] * (st * sc.z) + cb.z, fv[3] * (st * sc.w) + cb.w};
-                if (act != 0) {                   // wave-uniform
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) f[e] = apply_activation(f[e], act);
-                }
+                apply_activation_n<4>(f, act);    // act is wave-uniform
                 half4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
