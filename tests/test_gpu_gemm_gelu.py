@@ -157,3 +157,51 @@ def test_missing_fp16_output_needs_the_in_kernel_path(zq):
     with pytest.raises(zq.ZQError) as e:
         zq.zq_gemm_gelu_quant_tokenwise(xq, st, wq, sw, keep_g=False)
     assert e.value.code == 4
+
+
+def test_in_kernel_quantization_under_graph_replay(zq, orc):
+    """The launch generation of the in-kernel quantizer lives on the device, so a captured call can
+    be replayed: every replay, with new inputs copied into the captured buffers and eager calls of
+    other shapes in between, must give the bits of the two-kernel path on the same inputs."""
+    M, N, K, g = 1024, 2048, 512, 64
+    assert zq.gemm_quantizes_in_kernel(M, N, K, 8)
+    rng = zq_inputs.rng_for(8, 1)
+    _, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+    s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
+    xq_d = torch.zeros((M, K), dtype=torch.int8, device="cuda")
+    st_d, wq_d, sw_d, b_d = dev(s_tok), dev(wq), dev(s_w), dev(bias)
+    gq = torch.empty((M, N), dtype=torch.int8, device="cuda")
+    s2 = torch.empty(M, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False)
+    torch.cuda.synchronize()
+    other = _case(zq_inputs.rng_for(8, 2), 300, 400, 384, 25, 8)
+    for rep in range(4):
+        xq = zq_inputs.random_codes(zq_inputs.rng_for(8, 10 + rep), (M, K))
+        xq_d.copy_(dev(xq))
+        gq.zero_()
+        s2.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_q, got_s = host(gq).copy(), host(s2).copy()
+        # eager work of another shape between the replays, on the in-kernel path as well
+        prev_v = zq.force_gemm_variant(TILE128)
+        try:
+            zq.zq_gemm_gelu_quant_tokenwise(dev(other[0]), dev(other[1]), dev(other[5]), dev(other[2]), dev(other[3]))
+        finally:
+            zq.force_gemm_variant(prev_v)
+        prev = zq.set_in_kernel_quant(False)
+        try:
+            _, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d)
+            torch.cuda.synchronize()
+        finally:
+            zq.set_in_kernel_quant(prev)
+        assert_bit_equal(got_s, host(s_ref), "replay %d s_tok" % rep)
+        assert_bit_equal(got_q, host(q_ref), "replay %d codes" % rep)
+    assert zq.quant_wait_expired() == 0
