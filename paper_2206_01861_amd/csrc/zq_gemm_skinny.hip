@@ -398,24 +398,33 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
 
     // ---- dequantize this wave's 16 x (MT*16) strip and write it (App. D epilogue) ---------------
     const half4 bias4 = __builtin_bit_cast(half4, uint2{bias_lo, bias_hi});   // zeros without a bias
+    // A lane holds four columns of token r; stored from there, four consecutive lanes would write to
+    // four different rows.  One cross-lane permutation per dword puts the 32 contiguous bytes of a
+    // token's 16 columns into four consecutive lanes (token lane/4, columns 4*(lane%4)..), which the
+    // vector cache handles four times faster.  Every lane computes (rows past M from valid scales,
+    // never stored), because the permutation reads all lanes.
+    const int pull_out = 4 * ((lane % 4) * 16 + lane / 4);
+    const int n_st = strip * 16 + 4 * (lane % 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + r;
-        if (m < M) {
-            const float sc = __uint_as_float(st_bits[mt]) * sw;
-            float f[4];
+        const float sc = __uint_as_float(st_bits[mt]) * sw;
+        float f[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                f[e] = (float)acc[mt][e] * sc;
-                if (bias != nullptr) f[e] += (float)bias4[e];
-            }
-            apply_activation_n<4>(f, act);
-            half4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
-            *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
-            if (acc_out != nullptr) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n_col) = acc[mt];
+        for (int e = 0; e < 4; ++e) {
+            f[e] = (float)acc[mt][e] * sc;
+            if (bias != nullptr) f[e] += (float)bias4[e];
         }
+        apply_activation_n<4>(f, act);
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
+        uint2 ob = __builtin_bit_cast(uint2, o);
+        ob.x = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_out, (int)ob.x);
+        ob.y = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_out, (int)ob.y);
+        const int m_st = mt * 16 + lane / 4;
+        if (m_st < M) *reinterpret_cast<uint2 *>(out + (size_t)m_st * N + n_st) = ob;
+        const int m = mt * 16 + r;
+        if (acc_out != nullptr && m < M) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + n_col) = acc[mt];
     }
 #endif
 }
@@ -624,19 +633,23 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
     }
 
     const half4 bias4 = __builtin_bit_cast(half4, uint2{bias_lo, bias_hi});
+    // stores as in the INT8 kernel: a token's 16 columns from four consecutive lanes
+    const int pull_out = 4 * ((lane % 4) * 16 + lane / 4);
+    const int n_st = strip * 16 + 4 * (lane % 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + r;
-        if (m < M) {
-            half4 o;
+        half4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float f = acc[mt][e] * sw;
-                if (bias != nullptr) f += (float)bias4[e];
-                o[e] = (half_t)f;
-            }
-            *reinterpret_cast<half4 *>(out + (size_t)m * N + n_col) = o;
+        for (int e = 0; e < 4; ++e) {
+            float f = acc[mt][e] * sw;
+            if (bias != nullptr) f += (float)bias4[e];
+            o[e] = (half_t)f;
         }
+        uint2 ob = __builtin_bit_cast(uint2, o);
+        ob.x = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_out, (int)ob.x);
+        ob.y = (uint32_t)__builtin_amdgcn_ds_bpermute(pull_out, (int)ob.y);
+        const int m_st = mt * 16 + lane / 4;
+        if (m_st < M) *reinterpret_cast<uint2 *>(out + (size_t)m_st * N + n_st) = ob;
     }
 #endif
 }
