@@ -327,6 +327,19 @@ def time_gemm(zq, name, M, reps_target=40):
     gf = graph_of(lambda i: torch.nn.functional.linear(xf, wfs[i % len(wfs)], bias), reps)
     fbest = min(time_graph(gf, 3, reps, warm=1) for _ in range(2))
     del xf, wfs, gf, gq
+    # The vendor library's own INT8 GeMM (torch._int_mm -> hipBLASLt: INT32 output, no scales, no
+    # bias) on the prefill shapes, as a second comparator.
+    lib_int8 = None
+    if M > 128:
+        try:
+            xi = torch.randint(-127, 128, (M, K), device="cuda", dtype=torch.int8)
+            wi = torch.randint(-127, 128, (N, K), device="cuda", dtype=torch.int8).t()
+            torch._int_mm(xi, wi)
+            gi = graph_of(lambda i: torch._int_mm(xi, wi), 5)
+            lib_int8 = min(time_graph(gi, 2, 5, warm=1) for _ in range(2))
+            del xi, wi, gi
+        except Exception:                       # not every build routes _int_mm to a library kernel
+            lib_int8 = None
     ops = 2.0 * M * N * K
     bytes_min = M * K + wbytes + 4 * M + 4 * g + 2 * N + 2 * M * N
     variant = zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nws))
@@ -334,7 +347,9 @@ def time_gemm(zq, name, M, reps_target=40):
             "us": best * 1e3, "TOPS": ops / (best * 1e-3) / 1e12, "GBs": bytes_min / (best * 1e-3) / 1e9,
             "frac_int8_peak": ops / (best * 1e-3) / 1e12 / PEAK_INT8_TOPS,
             "frac_hbm_peak": bytes_min / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "fp16_us": fbest * 1e3, "speedup_vs_fp16": fbest / best, "rotating_sets": nset}
+            "fp16_us": fbest * 1e3, "speedup_vs_fp16": fbest / best, "rotating_sets": nset,
+            "lib_int8_us": None if lib_int8 is None else lib_int8 * 1e3,
+            "speedup_vs_lib_int8": None if lib_int8 is None else lib_int8 / best}
 
 
 def time_gemm_a16(zq, name, M, reps_target=40):
@@ -393,9 +408,10 @@ def run_table(args):
     for name, M in cases:
         r = time_gemm(zq, name, M)
         rows.append(r)
-        print("%-8s M=%-6d %-14s %9.1f us %8.1f TOPS %8.1f GB/s  int8 %.3f hbm %.3f  fp16 %8.1f us x%.2f" % (
+        lib = "" if r["lib_int8_us"] is None else "  lib int8 %8.1f us x%.2f" % (r["lib_int8_us"], r["speedup_vs_lib_int8"])
+        print("%-8s M=%-6d %-14s %9.1f us %8.1f TOPS %8.1f GB/s  int8 %.3f hbm %.3f  fp16 %8.1f us x%.2f%s" % (
             name, M, r["schedule"], r["us"], r["TOPS"], r["GBs"], r["frac_int8_peak"], r["frac_hbm_peak"],
-            r["fp16_us"], r["speedup_vs_fp16"]), file=sys.stderr, flush=True)
+            r["fp16_us"], r["speedup_vs_fp16"], lib), file=sys.stderr, flush=True)
         torch.cuda.empty_cache()
     # W8A16 on the QKV linears (the GeMM whose input the paper keeps in FP16 for its largest model)
     for name, M in cases:
