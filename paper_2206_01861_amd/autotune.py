@@ -82,7 +82,10 @@ def tune_shape(M, N, K, bits, m_lo=None, m_hi=None, verbose=False):
     m_hi = M if m_hi is None else m_hi
 
     candidates = []
-    for v in range(6):
+    v_count = 0
+    while zq.gemm_variant_name(v_count) is not None:
+        v_count += 1
+    for v in range(v_count):
         if v in (SKINNY, SKINNY_SPLITK):
             continue
         if zq.gemm_variant_name(v) == "simple" and M * N * K > (1 << 31):

@@ -11,7 +11,8 @@ std::atomic<int> g_forced_variant{-1};
 std::atomic<int> g_in_kernel_quant{1};
 
 inline bool is_tile_variant(int v) {
-    return v == zq::kGemmTile128 || v == zq::kGemmTile256 || v == zq::kGemmTile256x128;
+    return v == zq::kGemmTile128 || v == zq::kGemmTile256 || v == zq::kGemmTile256x128 ||
+           v == zq::kGemmTile256x192;
 }
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -248,6 +249,7 @@ const char *zq_gemm_variant_name(int variant) {
         case zq::kGemmSkinny: return "skinny";
         case zq::kGemmSkinnySplitK: return "skinny_splitk";
         case zq::kGemmTile256x128: return "tile256x128";
+        case zq::kGemmTile256x192: return "tile256x192";
     }
     return nullptr;
 }

@@ -59,6 +59,7 @@ bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t 
         case kGemmTile128:
         case kGemmTile256:
         case kGemmTile256x128:
+        case kGemmTile256x192:
             return true;                              // the last stage of a ragged K is zero filled
         case kGemmSkinny:
             return M <= kStreamMaxTokens && (K % 256) == 0;
@@ -75,6 +76,7 @@ hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st) {
         case kGemmTile128: return launch_gemm_tile(a, 128, st);
         case kGemmTile256: return launch_gemm_tile(a, 256, st);
         case kGemmTile256x128: return launch_gemm_tile(a, 192, st);
+        case kGemmTile256x192: return launch_gemm_tile(a, 256192, st);
         case kGemmSkinny: return launch_gemm_skinny(a, false, st);
         case kGemmSkinnySplitK: return launch_gemm_skinny(a, true, st);
     }
@@ -101,10 +103,24 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
     // Tiny problems (a BERT-base layer at 128 tokens) are all latency: one wave per 16x16 tile straight
     // from global memory starts and finishes sooner than a handful of LDS-tiled workgroups (6.2 vs 6.8 us).
     if ((long)M * N * K <= (1L << 27)) return kGemmSimple;
-    // 256x256 tiles once they fill the chip; 128x128 tiles waste less on ragged or small problems.
-    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-    if (t256 >= 160) return kGemmTile256;
-    return kGemmTile128;
+    // Tiled schedules.  The tiles of a launch all take the same time and a compute unit holds one of
+    // them (two of the four-wave 128x128 ones), so a launch lasts (rounds of tiles) x (time of a
+    // tile), and the time of a tile goes with its area times a factor for the operand bytes it moves
+    // per product.  Factors fitted to one-round measurements at K = 2048..6144 (256x256 = 1): 256x192
+    // 1.15, 128x128 on eight waves 1.85, two co-resident four-wave 128x128 tiles 4.1 each.  The
+    // 128x128 launcher itself takes eight waves up to 384 tiles and four beyond.
+    constexpr long kComputeUnits = 256;
+    const long rows256 = (M + 255) / 256;
+    const long t256 = rows256 * ((N + 255) / 256);
+    const long t192 = rows256 * ((N + 191) / 192);
+    const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    auto rounds = [](long tiles, long slots) { return (tiles + slots - 1) / slots; };
+    const long c256 = rounds(t256, kComputeUnits) * 65536 * 100;
+    const long c192 = rounds(t192, kComputeUnits) * 49152 * 115;
+    const long c128 = (t128 <= 384) ? rounds(t128, kComputeUnits) * 16384 * 185
+                                    : rounds(t128, 2 * kComputeUnits) * 16384 * 410;
+    if (c128 <= c256 && c128 <= c192) return kGemmTile128;
+    return (c192 < c256) ? kGemmTile256x192 : kGemmTile256;
 }
 
 extern "C" int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t workspace_bytes, int *row_blocks,

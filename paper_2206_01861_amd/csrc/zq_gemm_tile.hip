@@ -119,7 +119,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr int TPR4 = BK / 32;                    // INT4: threads per row (16 packed bytes each)
     constexpr int W4_ROWS = NT / TPR4;               // rows per pass
     constexpr int W4_PASSES = (BN + W4_ROWS - 1) / W4_ROWS;
-    static_assert(BN % W4_ROWS == 0 || BN < W4_ROWS, "INT4 passes must tile the weight rows");
 
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -229,7 +228,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         for (int p = 0; p < W4_PASSES; ++p) {
             const int row = p * W4_ROWS + (int)threadIdx.x / TPR4;
             const int q = (int)threadIdx.x % TPR4;
-            if (BN >= W4_ROWS || row < BN) {
+            if (BN % W4_ROWS == 0 || row < BN) {   // the last pass may reach past the tile
                 uint32_t d[8];
                 if (XT == 1) {
                     const uint32x4_t lo = __builtin_bit_cast(
@@ -382,7 +381,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     const int mw = m0 + wm * WM;              // first token row of this wave
     const int nw = n0 + wn * WN;              // first output column of this wave
     constexpr int LPR = WN * 2 / 16;          // lanes per output row (16 bytes each)
-    constexpr int RPI = 64 / LPR;             // rows per store instruction
+    static_assert((32 * LPR) % 64 == 0, "the 32-row block must be a whole number of store instructions");
     float rmax[FM];                           // QOUT: max |g| of this lane's token rows
     unsigned gen = 0;                         // QOUT: generation of this launch, back before it is needed
     if constexpr (QOUT == 1)
@@ -440,9 +439,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         // stores whole row segments.
         if (QOUT == 0 || out != nullptr) {
 #pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int row = i * RPI + lane / LPR;
-                const int col = (lane % LPR) * 8;
+            for (int i = 0; i < 32 * LPR / 64; ++i) {
+                const int row = (i * 64 + lane) / LPR;
+                const int col = ((i * 64 + lane) % LPR) * 8;
                 const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
                 const int m = mw + fm * 32 + row;
                 const int n = nw + col;
@@ -583,7 +582,8 @@ int quant_tile_edge(int M, int N) {
 
 }  // namespace
 
-// block: 256 = 256x256 tile, eight waves; 192 = 256x128 tile, four waves, two workgroups per CU;
+// block: 256 = 256x256 tile, eight waves; 256192 = 256x192 tile, eight waves (4 x 2, wave tile 64 x 96);
+//        192 = 256x128 tile, four waves, two workgroups per CU;
 //        128 = 128x128 tile: with at most one and a half tiles per CU, eight waves on a deep ring of
 //        128-byte stages (half the barriers per K, two waves per SIMD; measured 10-16 % faster there),
 //        otherwise four waves and 64 KB of LDS so that two workgroups share a CU.
@@ -591,6 +591,10 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     if (block == 256) {
         if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8>(a, st);
         return launch_tile_t<256, 256, 2, 4, 128, 2, 4>(a, st);
+    }
+    if (block == 256192) {
+        if (a.w_bits == 8) return launch_tile_t<256, 192, 4, 2, 128, 2, 8>(a, st);
+        return launch_tile_t<256, 192, 4, 2, 128, 2, 4>(a, st);
     }
     if (block == 192) {
         if (a.w_bits == 8) return launch_tile_t<256, 128, 2, 2, 64, 3, 8>(a, st);
@@ -643,9 +647,15 @@ hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
     a.wq = a16.wq; a.s_w = a16.s_w; a.groups = a16.groups; a.bias = a16.bias;
     a.M = a16.M; a.N = a16.N; a.K = a16.K; a.out = a16.out; a.acc_out = nullptr;
     a.workspace = nullptr; a.workspace_bytes = 0; a.w_bits = 8; a.act = 0;
-    const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (t256 >= 160) return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 1>(a, st);
-    return launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1>(a, st);
+    // the tile is chosen like the INT8 call's: rounds of tiles x area x a factor per tile shape
+    const long rows256 = (a.M + 255) / 256;
+    auto rounds = [](long tiles) { return (tiles + 255) / 256; };
+    const long c256 = rounds(rows256 * ((a.N + 255) / 256)) * 65536 * 100;
+    const long c192 = rounds(rows256 * ((a.N + 191) / 192)) * 49152 * 115;
+    const long c128 = rounds((long)((a.M + 127) / 128) * ((a.N + 127) / 128)) * 16384 * 185;
+    if (c128 <= c256 && c128 <= c192) return launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1>(a, st);
+    if (c192 < c256) return launch_tile_t<256, 192, 4, 2, 128, 2, 8, 1>(a, st);
+    return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 1>(a, st);
 }
 
 }  // namespace zq

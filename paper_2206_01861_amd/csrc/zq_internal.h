@@ -44,7 +44,8 @@ enum GemmVariant {
     kGemmSkinny = 3,      // M <= 128, K % 256 == 0: weight streaming, whole K in one workgroup
     kGemmSkinnySplitK = 4,// same, K also split across workgroups (needs workspace)
     kGemmTile256x128 = 5, // 256x128 block tile, four waves, two workgroups per CU
-    kGemmVariantCount = 6
+    kGemmTile256x192 = 6, // 256x192 block tile, eight waves: for grids that 256x256 tiles fill badly
+    kGemmVariantCount = 7
 };
 
 struct GemmArgs {

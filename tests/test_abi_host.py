@@ -52,6 +52,11 @@ def test_variant_table():
     assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws)) == "skinny_splitk"
     assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws - 1)) == "skinny"
     assert zq.gemm_workspace_bytes(4096, 4096, 1024) == 0
+    # 256-row tiles: 256 columns unless narrower tiles fill the 256 compute units better
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 4096, 1024)) == "tile256"       # 256 tiles: one round
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(2048, 6144, 2048)) == "tile256x192"   # 192 tiles -> 256
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 12288, 4096)) == "tile256"      # 768 tiles: three rounds
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(16384, 18432, 6144)) == "tile256"
 
 
 def test_stream_plan_covers_the_matrix():

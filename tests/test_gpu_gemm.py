@@ -10,7 +10,7 @@ from helpers import assert_bit_equal, assert_out_close, dev, freivalds_gpu, host
 
 pytestmark = pytest.mark.gpu
 
-SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK, TILE256X128 = range(6)
+SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK, TILE256X128, TILE256X192 = range(7)
 
 
 @pytest.fixture(scope="module")
@@ -73,6 +73,9 @@ SHAPES = [
     (TILE256, 70, 64, 4000, 4),
     (TILE256X128, 256, 128, 128, 8), (TILE256X128, 300, 400, 512, 25), (TILE256X128, 1030, 272, 256, 17),
     (TILE256X128, 17, 16, 384, 1), (TILE256X128, 512, 1024, 1024, 64),
+    # 256 x 192 tiles: whole and ragged in both directions, ragged K, a single tile
+    (TILE256X192, 256, 192, 128, 12), (TILE256X192, 300, 400, 512, 25), (TILE256X192, 1030, 768, 256, 48),
+    (TILE256X192, 17, 16, 384, 1), (TILE256X192, 515, 1200, 1056, 75), (TILE256X192, 2048, 6144, 128, 128),
     (SKINNY, 1, 64, 256, 4), (SKINNY, 3, 128, 768, 8), (SKINNY, 1, 2048, 2048, 128), (SKINNY, 8, 6144, 2048, 128),
     (SKINNY, 16, 208, 1280, 13), (SKINNY, 17, 80, 512, 5), (SKINNY, 32, 2048, 2048, 128),
     (SKINNY, 33, 144, 1792, 9), (SKINNY, 64, 1024, 1536, 64), (SKINNY, 50, 16, 256, 1),
@@ -116,7 +119,7 @@ def test_no_bias_and_extreme_codes(zq, orc):
     wq[1::2] = -127
     s_tok = np.full(M, 1e-3, np.float32)
     s_w = np.full(g, 1e-4, np.float32)
-    for variant in (SIMPLE, TILE128, TILE256, TILE256X128, SKINNY):
+    for variant in (SIMPLE, TILE128, TILE256, TILE256X128, TILE256X192, SKINNY):
         res = _run(zq, 8, variant, xq, s_tok, wq, s_w, None)
         acc = host(res[1])
         assert (acc[:, 0::2] == 16129 * K).all() and (acc[:, 1::2] == -16129 * K).all()
@@ -127,8 +130,8 @@ def test_largest_k_fills_the_accumulator(zq, orc):
     """K at the largest accepted values with every product at +-127*127: the INT32 accumulator ends
     within 0.01 % of its range and must not wrap in any schedule."""
     M, N, g = 3, 32, 2
-    for K, variants in ((133136, (SIMPLE, TILE128, TILE256, TILE256X128)),    # largest K the ABI takes (K % 16 == 0)
-                        (133120, (SIMPLE, TILE128, TILE256, TILE256X128, SKINNY, SKINNY_SPLITK))):
+    for K, variants in ((133136, (SIMPLE, TILE128, TILE256, TILE256X128, TILE256X192)),    # largest K the ABI takes (K % 16 == 0)
+                        (133120, (SIMPLE, TILE128, TILE256, TILE256X128, TILE256X192, SKINNY, SKINNY_SPLITK))):
         xq = np.full((M, K), 127, np.int8)
         xq[1] = -127
         wq = np.full((N, K), 127, np.int8)

@@ -30,7 +30,7 @@ def _check_fused(orc, g16, gq, s, xq, s_tok, codes, s_w, bias, approx, what):
 
 CASES = [
     (SIMPLE, 17, 768, 784, 48), (TILE128, 300, 400, 384, 25), (TILE128, 515, 1024, 1024, 64),
-    (TILE256, 300, 528, 512, 33), (TILE256X128, 300, 400, 512, 25), (SKINNY, 8, 6144, 2048, 128),
+    (TILE256, 300, 528, 512, 33), (TILE256X128, 300, 400, 512, 25), (6, 300, 400, 512, 25), (SKINNY, 8, 6144, 2048, 128),
     (SKINNY, 100, 768, 768, 48), (SKINNY_SPLITK, 33, 2064, 8192, 3), (-1, 128, 4096, 1024, 64),
     (-1, 16, 4096, 1024, 64),
 ]
