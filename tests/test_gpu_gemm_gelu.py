@@ -205,3 +205,34 @@ def test_in_kernel_quantization_under_graph_replay(zq, orc):
         assert_bit_equal(got_s, host(s_ref), "replay %d s_tok" % rep)
         assert_bit_equal(got_q, host(q_ref), "replay %d codes" % rep)
     assert zq.quant_wait_expired() == 0
+
+
+def test_in_kernel_quantization_while_another_stream_keeps_the_chip_busy(zq, orc):
+    """Tiles wait for the other tiles of their band, which is only safe because workgroups start in
+    id order: with another stream's GeMMs taking compute units away at the same time the call must
+    still finish with the right bits and without any wait running out."""
+    M, N, K, g = 4096, 4096, 512, 64
+    rng = zq_inputs.rng_for(9, 1)
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+    s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
+    args = (dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias))
+    assert zq.gemm_quantizes_in_kernel(M, N, K, 8)
+    prev = zq.set_in_kernel_quant(False)
+    try:
+        _, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)
+        torch.cuda.synchronize()
+    finally:
+        zq.set_in_kernel_quant(prev)
+    a = torch.randn((4096, 4096), device="cuda", dtype=torch.float16)
+    side = torch.cuda.Stream()
+    outs = []
+    with torch.cuda.stream(side):
+        for _ in range(40):
+            b = a @ a                                   # ~0.1 ms each on the other stream
+    for _ in range(12):
+        outs.append(zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False))
+    torch.cuda.synchronize()
+    assert zq.quant_wait_expired() == 0
+    for i, (_, q, s) in enumerate(outs):
+        assert_bit_equal(host(s), host(s_ref), "call %d s_tok" % i)
+        assert_bit_equal(host(q), host(q_ref), "call %d codes" % i)
