@@ -300,22 +300,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         }
     };
 
-    // Scale prefetch (App. D reads both scale vectors before the product is complete): the
-    // per-column weight-group scale and bias and the per-row token scale of this tile go to LDS now.
     float *col_scale = reinterpret_cast<float *>(smem + Cfg::kMain);
     float *col_bias = col_scale + BN;
     float *row_scale = col_bias + BN;
-    for (int c = threadIdx.x; c < BN; c += NT) {
-        int n = n0 + c;
-        if (n > N - 1) n = N - 1;
-        col_scale[c] = s_w[n / gs];
-        col_bias[c] = (bias != nullptr) ? (float)bias[n] : 0.0f;
-    }
-    for (int r = threadIdx.x; r < BM; r += NT) {
-        int m = m0 + r;
-        if (m > M - 1) m = M - 1;
-        row_scale[r] = (XT == 1) ? 1.0f : s_tok[m];   // FP16 activations carry no token scale
-    }
 
     // ---- main loop ----------------------------------------------------------
     // Stage kt lives in slot kt % NSTAGE.  During the last k step of stage kt every wave already holds
@@ -331,6 +318,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 w4_store(s);
             }
         }
+    }
+    // Scale prefetch (App. D reads both scale vectors before the product is complete): the
+    // per-column weight-group scale and bias and the per-row token scale of this tile go to LDS.
+    // They are requested after the first operand stages, and all three loads of a thread before
+    // any of them is used, so that their round trip runs under the operand loads instead of in
+    // front of them (it used to cost three dependent round trips before the first operand load).
+    static_assert(BN <= NT && BM <= NT, "one scale element per thread");
+    {
+        const int c = threadIdx.x;
+        int n = n0 + (c < BN ? c : 0);
+        if (n > N - 1) n = N - 1;
+        int m = m0 + (c < BM ? c : 0);
+        if (m > M - 1) m = M - 1;
+        const float sw_v = s_w[n / gs];
+        // without a bias the load reads a valid dummy address: no branch around a load in flight
+        const half_t b_v = *(bias != nullptr ? bias + n : reinterpret_cast<const half_t *>(s_w));
+        const float st_v = (XT == 1) ? 1.0f : s_tok[m];   // FP16 activations carry no token scale
+        if (c < BN) {
+            col_scale[c] = sw_v;
+            col_bias[c] = (bias != nullptr) ? (float)b_v : 0.0f;
+        }
+        if (c < BM) row_scale[c] = st_v;
     }
     if (!STAGED_W && nkt >= NSTAGE)
         wait_vmcnt<(NSTAGE - 1) * LPS>();      // stage 0 has landed; later stages may still be in flight
