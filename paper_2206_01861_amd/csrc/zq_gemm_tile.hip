@@ -15,11 +15,16 @@
 // wave overlap the matrix-core work of the other.
 //
 // The epilogue scales the INT32 accumulators by s_tok[row] * s_w[group], adds
-// the bias and rounds to FP16 (scales and bias were staged in LDS before the
-// main loop), passes 32 rows at a time through a wave-private LDS buffer and
-// writes full contiguous row segments.  INT4 weights are unpacked to INT8
-// (times 16) on their way into LDS and the factor is shifted out of the
-// accumulator.
+// the bias and rounds to FP16 (scales and bias were staged in LDS under the
+// first operand loads), passes 32 rows at a time through a wave-private LDS
+// buffer and writes full contiguous row segments.  INT4 weights are unpacked
+// to INT8 (times 16) on their way into LDS and the factor is shifted out of
+// the accumulator.
+//
+// QOUT = 1 adds the token-wise quantization of the output rows (App. A.2) to
+// the epilogue: the tiles of a band of token rows exchange their row maxima
+// through device memory and write INT8 codes from the accumulator registers
+// (see the state block below and the end of the kernel).
 //
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
