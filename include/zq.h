@@ -17,7 +17,13 @@
  * Conventions shared by every call
  *   - Every pointer is a DEVICE pointer owned by the caller, valid on the
  *     current HIP device, 16-byte aligned, and sized as documented.  The
- *     library allocates nothing, frees nothing and keeps no per-call state.
+ *     library allocates nothing and frees nothing.  It owns two small pieces
+ *     of device memory (file-scope arrays, one copy per device): arrival
+ *     counters of the K-split GeMM schedules and the exchange slots of the
+ *     GeMM calls that quantize their output inside the kernel.  Both are left
+ *     ready for the next call by the kernels themselves; calls that use the
+ *     same piece must not run at the same time on one device (see
+ *     zq_gemm_w8a16_dequant and zq_gemm_gelu_quant_tokenwise).
  *   - Matrices are dense row-major.  "fp16" is IEEE binary16.
  *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream)
  *     and the call returns without synchronising.  Outputs must not alias
