@@ -23,7 +23,7 @@
  *     GeMM calls that quantize their output inside the kernel.  Both are left
  *     ready for the next call by the kernels themselves; calls that use the
  *     same piece must not run at the same time on one device (see
- *     zq_gemm_w8a16_dequant and zq_gemm_gelu_quant_tokenwise).
+ *     zq_gemm_i8_dequant and zq_gemm_gelu_quant_tokenwise).
  *   - Matrices are dense row-major.  "fp16" is IEEE binary16.
  *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream)
  *     and the call returns without synchronising.  Outputs must not alias
@@ -126,7 +126,9 @@ size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
  *             quantization of the FP16-rounded `out`, ready for the next GeMM.
  *   workspace NULL, or device scratch of workspace_bytes.  With less than
  *             zq_gemm_workspace_bytes(...) the call still succeeds, on a
- *             kernel that needs none.
+ *             kernel that needs none.  Calls that use it (K split) share the
+ *             library's arrival counters and must not overlap with each other
+ *             on one device.
  */
 zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w,
                              int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
