@@ -292,6 +292,17 @@ int zq_tune_count(void);
 int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t workspace_bytes, int *row_blocks, int *k_splits,
                         int *consumers);
 
+/*
+ * Into how many K ranges the streaming schedule divides each strip inside a
+ * workgroup for the cut zq_gemm_stream_plan reports: 1, or 2 (INT8 weights, at
+ * most 32 tokens, no K split, few strips per CU and K of 4096 or more: each
+ * strip is then streamed by two waves over halves of K, which doubles the
+ * loads a CU keeps in flight, and their INT32 accumulators are added before
+ * the epilogue, so results do not change).  Host-only; launches nothing.
+ * Returns 0 for a shape these schedules do not take.
+ */
+int zq_gemm_stream_k_ranges(int M, int N, int K, int w_bits, size_t workspace_bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     quant_wait_expired,
     set_in_kernel_quant,
     gemm_stream_plan,
+    gemm_stream_k_ranges,
     gemm_variant_name,
     gemm_workspace_bytes,
     force_gemm_variant,

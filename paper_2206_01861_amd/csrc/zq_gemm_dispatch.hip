@@ -15,7 +15,8 @@ hipError_t launch_gemm_simple(const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st);
 hipError_t launch_gemm_skinny(const GemmArgs &a, bool split_k, hipStream_t st);
 size_t stream_workspace_bytes(int M, int N, int K, int w_bits);
-void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers);
+void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers,
+                 int *k_ranges);
 
 // Measured overrides of the built-in choices (the profiler-driven schedule search of App. D, kept
 // as a table the caller fills): exact (N, K, bits), a range of M.
@@ -130,8 +131,19 @@ extern "C" int zq_gemm_stream_plan(int M, int N, int K, int w_bits, size_t works
     if (M <= 0 || M > kStreamMaxTokens || N <= 0 || (N % 16) != 0 || K <= 0 || (K % 256) != 0 || (w_bits != 8 && w_bits != 4))
         return ZQ_ERR_UNSUPPORTED;
     const bool split = workspace_bytes > 0 && workspace_bytes >= stream_workspace_bytes(M, N, K, w_bits);
-    stream_plan(M, N, K, w_bits, split, row_blocks, k_splits, consumers);
+    int k_ranges = 1;
+    stream_plan(M, N, K, w_bits, split, row_blocks, k_splits, consumers, &k_ranges);
     return ZQ_OK;
+}
+
+extern "C" int zq_gemm_stream_k_ranges(int M, int N, int K, int w_bits, size_t workspace_bytes) {
+    using namespace zq;
+    if (M <= 0 || M > kStreamMaxTokens || N <= 0 || (N % 16) != 0 || K <= 0 || (K % 256) != 0 || (w_bits != 8 && w_bits != 4))
+        return 0;
+    const bool split = workspace_bytes > 0 && workspace_bytes >= stream_workspace_bytes(M, N, K, w_bits);
+    int row_blocks = 0, k_splits = 0, consumers = 0, k_ranges = 1;
+    stream_plan(M, N, K, w_bits, split, &row_blocks, &k_splits, &consumers, &k_ranges);
+    return k_ranges;
 }
 
 extern "C" int zq_tune_set(int m_lo, int m_hi, int N, int K, int w_bits, int variant, int row_blocks, int k_splits) {

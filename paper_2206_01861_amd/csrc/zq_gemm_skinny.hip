@@ -159,9 +159,12 @@ struct StreamPlan {
     int consumers;    // consumer waves per workgroup = most strips in a row block
     // filled by finish_plan(): strips / row_blocks, strips % row_blocks, stages / k_splits, stages % k_splits
     int strips_per_block, strips_rem, stages_per_split, stages_rem;
+    // 1: every strip of a row block is streamed by two waves, each over half of the block's K
+    // range, and their accumulators are added through LDS at the end (see plan_stream)
+    int range_shift = 0;
 };
 
-template <int MT, int WBITS, int DW, int R>
+template <int MT, int WBITS, int DW, int R, int QSH = 0>
 __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
@@ -187,7 +190,10 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int k_lo = ks * plan.stages_per_split + (ks < plan.stages_rem ? ks : plan.stages_rem);
     const int k_hi = k_lo + plan.stages_per_split + (ks < plan.stages_rem ? 1 : 0);
     const int n = k_hi - k_lo;                        // stages of this workgroup (>= 1: k_splits <= stages)
-    const int npad = (n + DW - 1) / DW * DW;          // the pipeline always runs whole groups of DW
+    constexpr int Q = 1 << QSH;                       // K ranges per strip (1, or 2 with QSH = 1)
+    const int nq = (n + Q - 1) >> QSH;                // stages per range = steps of this workgroup
+    const int npad = (nq + DW - 1) / DW * DW;         // the pipeline always runs whole groups of DW
+    constexpr int SLOT = X_STAGE << QSH;              // a ring slot holds the activation stage of every range
 
     if (wave == 0) {
         // ---- producer: activation stages into the LDS ring ------------------
@@ -203,35 +209,49 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
             if (grow > M - 1) grow = M - 1;           // rows past M: valid data, results never stored
             voff[u] = grow * K + (((lane % 16) ^ (row & 15)) * 16);
         }
+        // step i of range q is stage q*nq + i of this workgroup (past the end: the last stage again,
+        // loaded and never multiplied)
         auto issue_x = [&](int i, int slot) __attribute__((always_inline)) {
-            uint8_t *base = smem + slot * X_STAGE;
-            const int soff = (k_lo + i) * kStageK;
 #pragma unroll
-            for (int u = 0; u < LX; ++u)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[u], soff, 0, 0);
+            for (int q = 0; q < Q; ++q) {
+                uint8_t *base = smem + slot * SLOT + q * X_STAGE;
+                int stg = q * nq + i;
+                if (Q > 1 && stg > n - 1) stg = n - 1;
+                const int soff = (k_lo + stg) * kStageK;
+#pragma unroll
+                for (int u = 0; u < LX; ++u)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, voff[u], soff, 0,
+                                                             0);
+            }
         };
+        static_assert((R - 2) * LX * Q <= 63, "the wait count is a six-bit field");
 #pragma unroll
         for (int s = 0; s < R - 1; ++s)
-            if (s < n) issue_x(s, s);
+            if (s < nq) issue_x(s, s);
         for (int i = 0; i < npad; ++i) {
-            if (i < n) {
-                // Stage i has landed once at most the R-2 later stages are outstanding.
-                if (i + R - 2 < n)
-                    wait_vmcnt<(R - 2) * LX>();
+            if (i < nq) {
+                // Step i has landed once at most the loads of the R-2 later steps are outstanding.
+                if (i + R - 2 < nq)
+                    wait_vmcnt<(R - 2) * LX * Q>();
                 else
                     wait_vmcnt<0>();
             }
             lds_barrier();                            // slot i filled; slot i-1 drained by every consumer
-            if (i + R - 1 < n) issue_x(i + R - 1, (i + R - 1) % R);
+            if (i + R - 1 < nq) issue_x(i + R - 1, (i + R - 1) % R);
         }
         return;
     }
 
-    const int strip = s_lo + wave - 1;
+    const int cidx = wave - 1;                        // consumer: (strip of the block, K range)
+    const int q = cidx & (Q - 1);
+    const int strip = s_lo + (cidx >> QSH);
     if (strip >= s_hi) {                              // no strip for this wave: keep the barrier count
         for (int i = 0; i < npad; ++i) lds_barrier();
         return;
     }
+    int n_mine = n - q * nq;                          // stages of this wave's range
+    n_mine = n_mine < 0 ? 0 : (n_mine > nq ? nq : n_mine);
+    const int stg_last = n_mine > 0 ? q * nq + n_mine - 1 : n - 1;
 
     // ---- consumers: weight strip through registers ------------------------
     const int wrow_bytes = (WBITS == 8) ? K : K / 2;
@@ -243,8 +263,9 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     int32x4 wreg[DW][LW];
     // Stage i of this workgroup; indices past the end re-load the last stage (never computed).
     auto issue_w = [&](int i, int32x4(&dst)[LW]) __attribute__((always_inline)) {
-        if (i > n - 1) i = n - 1;
-        const int soff = __builtin_amdgcn_readfirstlane((k_lo + i) * W_STAGE_BYTES);   // wave-uniform by construction
+        int stg = q * nq + i;
+        if (stg > stg_last) stg = stg_last;
+        const int soff = __builtin_amdgcn_readfirstlane((k_lo + stg) * W_STAGE_BYTES);   // wave-uniform by construction
         issue_strip<LW>(dst, voff_w, rs_w, soff);
     };
 
@@ -292,7 +313,7 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     // freed with the stage DW further on; the last group only drains.
     int i = 0;
     auto step_compute = [&](const int32x4(&w)[LW]) __attribute__((always_inline)) {
-        if (i < n) compute(w, smem + (i % R) * X_STAGE);
+        if (i < n_mine) compute(w, smem + (i % R) * SLOT + q * X_STAGE);
     };
 #pragma unroll
     for (int d = 0; d < DW; ++d) issue_w(d, wreg[d]);
@@ -341,6 +362,24 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     drain(std::integral_constant<int, 5>{});
     drain(std::integral_constant<int, 6>{});
     drain(std::integral_constant<int, 7>{});
+
+    // ---- K ranges of one strip: add the accumulators through LDS; range 0 carries on -----------
+    // (waves that have ended, the producer among them, no longer count at a barrier)
+    if constexpr (Q > 1) {
+        lds_barrier();                                // every wave is past its last fragment read: the ring is free
+        int32x4 *part = reinterpret_cast<int32x4 *>(smem) + (size_t)cidx * MT * kWave + lane;
+        if (q != 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) part[mt * kWave] = acc[mt];
+        }
+        lds_barrier();
+        if (q != 0) return;
+#pragma unroll
+        for (int o = 1; o < Q; ++o) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] += part[(o * MT + mt) * kWave];
+        }
+    }
 
     landed(sw_bits);                                  // the drain ended with vmcnt(0)
     landed(bias_lo);
@@ -668,7 +707,7 @@ int stream_depth(int w_bits) { return w_bits == 8 ? 4 : 8; }   // a stage of a s
 // at most kCuRate bytes per microsecond, and no more than its consumers keep in flight over one
 // memory latency; the CU with the most bytes sets the time; activation loads share the CU's load
 // path in proportion to token tiles per consumer; a K split costs the exchange round trips.
-StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
+StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split, bool allow_ranges = true) {
     const int S = N / 16, St = K / kStageK, mt = token_tiles(M);
     const double kCuRate = 24e3, kStart = 4.0, kExchange = 4.5, kExchangeRate = 3e6;
     // memory latency in microseconds: about 1 on a quiet chip, 2 with 32 MB streaming, 4 beyond 80 MB
@@ -679,6 +718,19 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     const double inflight = stream_depth(w_bits) * stage_bytes;   // per consumer wave
     StreamPlan best{S, St, 0, 1, 1};
     double best_t = 1e30;
+    // Two K ranges per strip (two waves per strip, accumulators added through LDS): measured to pay
+    // for INT8 weights at up to 32 tokens when a CU has at most three strips and the K range of a
+    // workgroup is at least 16 stages long (at one token 2048x4096 6.4 -> 5.0 us, 4096x4096 7.6 ->
+    // 6.0 us, 12288x4096 13.4 -> 12.1 us); with shorter K or INT4 weights the single producer wave,
+    // which then supplies two activation stages per step, and the larger workgroups cost more than
+    // the extra streams bring.  They are only weighed against other cuts without a K split, and
+    // only given to a cut without one: where the split wins without them it also wins with them
+    // (8192-deep 2048x2048: 7.3 us split four ways, 8.3 us with ranges).
+    bool ranges_on = false;
+    auto range_rule = [&](int c, int st) {
+        return (w_bits == 8 && mt <= 2 && st >= 16 && S <= 3 * kCUs && 2 * c <= kMaxConsumers) ? 1 : 0;
+    };
+    auto range_shift_for = [&](int c, int st) { return ranges_on ? range_rule(c, st) : 0; };
     auto consider = [&](int row_blocks, int k_splits) {
         if (row_blocks < 1 || row_blocks > S || k_splits < 1 || k_splits > St) return;
         const int c = (S + row_blocks - 1) / row_blocks;
@@ -688,10 +740,12 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
         const long wgs = (long)row_blocks * k_splits;
         const int per_cu = (int)((wgs + kCUs - 1) / kCUs);
         const int st = (St + k_splits - 1) / k_splits;
-        double rate = c * per_cu * inflight / latency;
+        const int waves = c << range_shift_for(c, St / k_splits);   // streams per workgroup
+        double rate = waves * per_cu * inflight / latency;
         if (rate > kCuRate) rate = kCuRate;
         const double bytes_cu = (double)per_cu * c * st * stage_bytes * (1.0 + 0.3 * mt / c);
         double t = kStart + bytes_cu / rate;
+        if (waves > c) t += 0.3;                    // the accumulators of a strip's ranges meet in LDS
         if (k_splits > 1)                           // round trips, then the partials written and read back
             t += kExchange + 0.3 * k_splits + 2.0 * k_splits * M * N * 4.0 / kExchangeRate;
         // near-ties go to the cut that spreads over more CUs
@@ -708,6 +762,13 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     }
     for (int m = 1; m <= 8; ++m)
         for (int ksp = 1; ksp <= 4; ++ksp) consider(kCUs * m / ksp, ksp);   // whole multiples of the CU count
+    if (allow_ranges && best.k_splits == 1) {        // second pass: the unsplit cuts again, now with two ranges
+        ranges_on = true;
+        best_t = 1e30;
+        best = StreamPlan{S, St, 0, 1, 1};
+        for (int c = 1; c <= kMaxConsumers; ++c) consider((S + c - 1) / c, 1);
+        for (int m = 1; m <= 8; ++m) consider(kCUs * m, 1);
+    }
     int trb = 0, tks = 0;
     if (tuned_stream_plan(M, N, K, w_bits, &trb, &tks) && (tks == 1 || allow_split))   // validated when registered
         best = StreamPlan{S, St, trb, tks, (S + trb - 1) / trb};
@@ -718,22 +779,33 @@ StreamPlan plan_stream(int M, int N, int K, int w_bits, bool allow_split) {
     best.strips_rem = S % best.row_blocks;
     best.stages_per_split = St / best.k_splits;
     best.stages_rem = St % best.k_splits;
+    best.range_shift = (allow_ranges && best.k_splits == 1) ? range_rule(best.consumers, best.stages_per_split) : 0;
     return best;
 }
 
-template <int MT, int WBITS>
-hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_t st) {
+template <int MT, int WBITS, int QSH>
+hipError_t launch_stream_q(const GemmArgs &a, const StreamPlan &plan, hipStream_t st) {
     constexpr int R = 3;
     constexpr int DW = (WBITS == 8) ? 4 : 8;
-    constexpr size_t lds = (size_t)R * MT * 16 * kStageK;
+    constexpr size_t lds = ((size_t)R * MT * 16 * kStageK) << QSH;
     static std::atomic<uint64_t> configured{0};
-    const void *kernel = reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R>);
+    const void *kernel = reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R, QSH>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R>), dim3(plan.row_blocks, plan.k_splits),
-                       dim3(64 * (plan.consumers + 1)), lds, st, a.xq, a.s_tok, reinterpret_cast<const uint8_t *>(a.wq),
-                       a.s_w, a.N / a.groups, reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K,
-                       reinterpret_cast<half_t *>(a.out), a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan, a.act);
+    if ((plan.consumers << QSH) > kMaxConsumers) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R, QSH>), dim3(plan.row_blocks, plan.k_splits),
+                       dim3(64 * ((plan.consumers << QSH) + 1)), lds, st, a.xq, a.s_tok,
+                       reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
+                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
+                       a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan, a.act);
     return hipGetLastError();
+}
+template <int MT, int WBITS>
+hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_t st) {
+    if constexpr (WBITS == 8 && MT <= 2) {            // the only combinations the planner gives two ranges
+        if (plan.range_shift == 1) return launch_stream_q<MT, WBITS, 1>(a, plan, st);
+    }
+    if (plan.range_shift != 0) return hipErrorInvalidValue;
+    return launch_stream_q<MT, WBITS, 0>(a, plan, st);
 }
 
 }  // namespace
@@ -747,11 +819,13 @@ size_t stream_workspace_bytes(int M, int N, int K, int w_bits) {
     return (size_t)plan.k_splits * M * N * sizeof(int32_t);
 }
 
-void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers) {
+void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers,
+                 int *k_ranges) {
     const StreamPlan plan = plan_stream(M, N, K, w_bits, allow_split);
     *row_blocks = plan.row_blocks;
     *k_splits = plan.k_splits;
     *consumers = plan.consumers;
+    *k_ranges = 1 << plan.range_shift;
 }
 
 namespace {
@@ -773,7 +847,11 @@ hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStre
 
 // FP16 activations: the same cut as the INT8 call of the same shape (the weight stream is the same).
 hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st) {
-    const StreamPlan plan = plan_stream(a.M, a.N, a.K, 8, allow_split);
+    StreamPlan plan = plan_stream(a.M, a.N, a.K, 8, allow_split, false);   // this kernel has no K ranges
+    // Without ranges the planner may want more K splits than the INT8 call whose workspace size the
+    // caller was told: never split further than the workspace holds.
+    if (plan.k_splits > 1 && (size_t)plan.k_splits * a.M * a.N * sizeof(float) > a.workspace_bytes)
+        plan = plan_stream(a.M, a.N, a.K, 8, false, false);
     const int mt = token_tiles(a.M);
     if (mt <= 1) return launch_stream_a16_t<1>(a, plan, st);
     if (mt <= 2) return launch_stream_a16_t<2>(a, plan, st);

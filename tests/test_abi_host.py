@@ -85,6 +85,31 @@ def test_stream_plan_covers_the_matrix():
         zq.gemm_stream_plan(8, 1024, 1000)
 
 
+def test_stream_k_ranges_only_where_they_apply():
+    """Two K ranges per strip: INT8 weights, at most 32 tokens, no K split, at least 4096 deep,
+    and at most four strips per workgroup (two waves each, eight consumer waves at most)."""
+    import random
+    rnd = random.Random(11)
+    assert zq.gemm_stream_k_ranges(1, 4096, 4096, 8, 0) == 2
+    assert zq.gemm_stream_k_ranges(16, 12288, 4096, 8, 0) == 2
+    assert zq.gemm_stream_k_ranges(1, 4096, 4096, 4, 0) == 1          # INT4 weights
+    assert zq.gemm_stream_k_ranges(33, 4096, 4096, 8, 0) == 1         # more than two token tiles
+    assert zq.gemm_stream_k_ranges(1, 4096, 2048, 8, 0) == 1          # K too short
+    assert zq.gemm_stream_k_ranges(129, 4096, 4096, 8, 0) == 0 and zq.gemm_stream_k_ranges(1, 4096, 1000, 8, 0) == 0
+    seen = 0
+    for _ in range(300):
+        M, N, K, bits = rnd.randint(1, 128), 16 * rnd.randint(1, 1500), 256 * rnd.randint(1, 100), rnd.choice([4, 8])
+        ws = zq.gemm_workspace_bytes(M, N, K, bits)
+        for offered in (0, ws):
+            r = zq.gemm_stream_k_ranges(M, N, K, bits, offered)
+            rb, ks, c = zq.gemm_stream_plan(M, N, K, bits, offered)
+            assert r in (1, 2)
+            if r == 2:
+                seen += 1
+                assert bits == 8 and M <= 32 and ks == 1 and K >= 4096 and c <= 4 and N <= 3 * 256 * 16
+    assert seen > 0
+
+
 def test_weight_quant_validation():
     f = zq.lib().zq_quantize_weight_groupwise
     assert f(None, 64, 64, 4, 8, P, P, None) == E_NULL

@@ -83,6 +83,10 @@ SHAPES = [
     (SKINNY, 65, 256, 512, 16), (SKINNY, 100, 768, 768, 48), (SKINNY, 128, 2048, 2048, 128), (SKINNY, 113, 144, 1792, 9),
     # strips dealt unevenly over the row blocks, up to eight consumer waves per workgroup
     (SKINNY, 64, 18432, 1024, 128), (SKINNY, 16, 33040, 512, 5), (SKINNY, 9, 4112, 768, 1),
+    # deep K without a split: two K ranges per strip for INT8 weights (even and odd stage counts, uneven
+    # strips per row block, one to four strips per workgroup)
+    (SKINNY, 1, 2048, 4096, 128), (SKINNY, 32, 1040, 4352, 65), (SKINNY, 17, 4112, 8192, 1), (SKINNY, 5, 80, 6400, 5),
+    (SKINNY, 16, 12288, 4096, 96), (SKINNY, 9, 10000, 4864, 25),
     # K split 3- to 12-fold, with ragged strip counts
     (SKINNY_SPLITK, 1, 2048, 8192, 128), (SKINNY_SPLITK, 8, 256, 4096, 16), (SKINNY_SPLITK, 32, 2048, 8192, 128),
     (SKINNY_SPLITK, 64, 1024, 6144, 64), (SKINNY_SPLITK, 13, 80, 2304, 5), (SKINNY_SPLITK, 33, 2064, 8192, 3),
@@ -107,6 +111,8 @@ def test_gemm_against_oracle(zq, orc, bits, variant, M, N, K, g):
         if nbytes == 0:
             pytest.skip("shape does not split")
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    if variant == SKINNY and bits == 8 and M <= 32 and K >= 4096:
+        assert zq.gemm_stream_k_ranges(M, N, K, bits, 0) == 2
     res = _run(zq, bits, variant, xq, s_tok, wq, s_w, bias, workspace=ws)
     _check(orc, res, xq, s_tok, codes, s_w, bias, "%s %d-bit %dx%dx%d" % (zq.gemm_variant_name(variant), bits, M, N, K))
 
@@ -282,3 +288,21 @@ def test_autotune_registers_a_runnable_schedule(zq, orc):
         finally:
             zq.tune_clear()
         assert zq.gemm_choose_variant(M, N, K, bits, zq.gemm_workspace_bytes(M, N, K, bits)) == base
+
+
+def test_two_k_ranges_with_four_strips_per_workgroup(zq, orc):
+    """The fullest workgroup of the two-range streaming schedule: four strips, eight consumer waves,
+    strips dealt unevenly (65 over 17 row blocks).  The built-in cuts stop at three strips per
+    workgroup where ranges apply, so the cut comes from the schedule table."""
+    M, N, K, g = 8, 1040, 4096, 65
+    rng = zq_inputs.rng_for(4, 83)
+    xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+    zq.tune_clear()
+    try:
+        zq.tune_set(1, 32, N, K, 8, SKINNY, 17, 1)
+        assert zq.gemm_stream_plan(M, N, K, 8, 0) == (17, 1, 4)
+        assert zq.gemm_stream_k_ranges(M, N, K, 8, 0) == 2
+        res = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias)
+        _check(orc, res, xq, s_tok, codes, s_w, bias, "two ranges, four strips")
+    finally:
+        zq.tune_clear()
