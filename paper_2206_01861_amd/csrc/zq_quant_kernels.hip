@@ -55,14 +55,20 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
     const int nvec = K >> 3;
     const half8 *rin = in + (size_t)row * nvec;
 
+    constexpr bool kGelu = (OP == kOpGeluErf || OP == kOpGeluTanh);
     float v[VPT][8];
+    uint32x4_t raw[VPT];                     // GeLU: the FP16 pairs as loaded, converted where the bias is added
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
         const int idx = i * TPR + t;
         if (idx < nvec) {
             half8 h = rin[idx];
+            if (kGelu) {
+                raw[i] = __builtin_bit_cast(uint32x4_t, h);
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[i][e] = (float)h[e];
+                for (int e = 0; e < 8; ++e) v[i][e] = (float)h[e];
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[i][e] = 0.0f;
@@ -104,15 +110,19 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
                 }
             }
         }
-    } else if (OP == kOpGeluErf || OP == kOpGeluTanh) {
+    } else if (kGelu) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const int idx = i * TPR + t;
             if (idx < nvec) {
                 if (p0 != nullptr) {
-                    half8 b = p0[idx];
+                    const uint32x4_t b = __builtin_bit_cast(uint32x4_t, p0[idx]);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[i][e] += (float)b[e];
+                    for (int d = 0; d < 4; ++d) add2_f16_f32(raw[i][d], b[d], v[i][2 * d], v[i][2 * d + 1]);
+                } else {
+                    const half8 h = __builtin_bit_cast(half8, raw[i]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[i][e] = (float)h[e];
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[i][e] = (OP == kOpGeluErf) ? gelu_erf(v[i][e]) : gelu_tanh(v[i][e]);

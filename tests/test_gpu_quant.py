@@ -125,6 +125,28 @@ def test_gelu_quant(zq, orc, approx, M, N):
     check_fused_codes(host(xq_nb), host(s_nb), host(y_nb), y64_nb, "gelu no bias")
 
 
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_gelu_of_every_fp16_input(zq, orc, with_bias):
+    """The kernel's GeLU (erf form) over all 63488 finite FP16 inputs, alone and with a bias that
+    moves them off the FP16 grid: within 2.5e-7 + 2e-6 |y| of the fp64 value (the kernel's
+    approximation is good to 1.2e-7 absolute; the relative term covers fp32 rounding of large values).
+    Subnormal inputs and both zeros included."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    h = bits.view(np.float16)
+    h = h[np.isfinite(h)]
+    pad = (-h.size) % 4096
+    h = np.concatenate([h, np.zeros(pad, np.float16)]).reshape(-1, 4096)
+    bias = None
+    if with_bias:
+        bias = zq_inputs.bias(zq_inputs.rng_for(3, 4242), 4096, std=0.37)
+    _, _, y = zq.zq_gelu_quant_tokenwise(dev(h), None if bias is None else dev(bias), y_dtype=torch.float32)
+    y = host(y).astype(np.float64)
+    y64, _ = orc.gelu(h, bias)
+    err = np.abs(y - y64)
+    tol = 2.5e-7 + 2e-6 * np.abs(y64)
+    assert (err <= tol).all(), "worst %.3e at h=%r" % ((err - tol).max(), h.ravel()[(err - tol).argmax()])
+
+
 @pytest.mark.parametrize("M,K", [(1, 16), (5, 768), (64, 4096), (3, 32768), (130, 1040)])
 def test_standalone_tokenwise_quantizer(zq, orc, M, K):
     """The quantization operator on its own (Sec. 4.3): bit-exact against the oracle, zero rows included."""
