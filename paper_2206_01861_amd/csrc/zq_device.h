@@ -17,16 +17,42 @@ typedef uint32_t uint32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 
+// One cross-lane move on the data-parallel-primitive path (no LDS crossbar, a few cycles): every lane
+// receives the value of the lane that CTRL names within its row of 16.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// The value that lane `lane` holds, as a scalar.
+__device__ __forceinline__ float read_lane(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // row_half_mirror: lane i of each 8 <- lane 7 - i
+constexpr int kDppMirror = 0x140;       // row_mirror: lane i of each 16 <- lane 15 - i
+
+// Reductions over the 64 lanes of a wave; every lane must be active and every lane gets the result.
+// Four steps inside each row of 16 lanes (after each, the lanes that have been combined hold the same
+// bits, since both partners add or compare the same two values), then the four row results are read
+// as scalars.  A butterfly of six ds_bpermute round trips is several hundred cycles of latency per
+// reduction, which the row kernels (one short pass per row) cannot hide.
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+    v = fmaxf(v, dpp_move<kDppXor1>(v));
+    v = fmaxf(v, dpp_move<kDppXor2>(v));
+    v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_move<kDppMirror>(v));
+    const float r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
+    v += dpp_move<kDppMirror>(v);
+    const float r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    return (r0 + r1) + (r2 + r3);
 }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
