@@ -56,22 +56,42 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
     const half8 *rin = in + (size_t)row * nvec;
 
     constexpr bool kGelu = (OP == kOpGeluErf || OP == kOpGeluTanh);
-    float v[VPT][8];
-    uint32x4_t raw[VPT];                     // GeLU: the FP16 pairs as loaded, converted where the bias is added
+    // Every load of the row and (for up to four vectors per thread) of its parameters is issued before
+    // the first result is waited for: vectors past the end of the row read vector 0 instead of being
+    // skipped, so that no branch separates the loads and one memory round trip covers them all.
+    constexpr bool kPre = (VPT <= 4) && (OP == kOpLayerNorm || kGelu);
+    bool ok[VPT];
+    int idc[VPT];
+    uint32x4_t raw[VPT];
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
         const int idx = i * TPR + t;
-        if (idx < nvec) {
-            half8 h = rin[idx];
-            if (kGelu) {
-                raw[i] = __builtin_bit_cast(uint32x4_t, h);
-            } else {
+        ok[i] = idx < nvec;
+        idc[i] = ok[i] ? idx : 0;
+        raw[i] = __builtin_bit_cast(uint32x4_t, rin[idc[i]]);
+    }
+    uint32x4_t pa[kPre ? VPT : 1], pb[kPre ? VPT : 1];
+    if (kPre && OP == kOpLayerNorm) {
+        // gamma is always there; without beta, gamma is loaded a second time (a cache hit) and not
+        // used, which keeps the loads free of branches
+        const half8 *q1 = p1 != nullptr ? p1 : p0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[i][e] = (float)h[e];
-            }
-        } else {
+        for (int i = 0; i < (kPre ? VPT : 0); ++i) {
+            pa[i] = __builtin_bit_cast(uint32x4_t, p0[idc[i]]);
+            pb[i] = __builtin_bit_cast(uint32x4_t, q1[idc[i]]);
+        }
+    } else if (kPre && p0 != nullptr) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[i][e] = 0.0f;
+        for (int i = 0; i < (kPre ? VPT : 0); ++i) pa[i] = __builtin_bit_cast(uint32x4_t, p0[idc[i]]);
+    }
+
+    float v[VPT][8];
+    if (!kGelu) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const half8 h = __builtin_bit_cast(half8, raw[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = ok[i] ? (float)h[e] : 0.0f;
         }
     }
 
@@ -85,7 +105,7 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
         float ss = 0.0f;
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            if (i * TPR + t < nvec) {
+            if (ok[i]) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     float d = v[i][e] - mean;
@@ -97,11 +117,10 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
         const float rstd = 1.0f / sqrtf(var + eps);
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int idx = i * TPR + t;
-            if (idx < nvec) {
-                half8 g = p0[idx];
+            if (ok[i]) {
+                const half8 g = kPre ? __builtin_bit_cast(half8, pa[kPre ? i : 0]) : p0[idc[i]];
                 if (p1 != nullptr) {
-                    half8 b = p1[idx];
+                    const half8 b = kPre ? __builtin_bit_cast(half8, pb[kPre ? i : 0]) : p1[idc[i]];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[i][e] = (v[i][e] - mean) * rstd * (float)g[e] + (float)b[e];
                 } else {
@@ -113,10 +132,9 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
     } else if (kGelu) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int idx = i * TPR + t;
-            if (idx < nvec) {
+            if (ok[i]) {
                 if (p0 != nullptr) {
-                    const uint32x4_t b = __builtin_bit_cast(uint32x4_t, p0[idx]);
+                    const uint32x4_t b = kPre ? pa[kPre ? i : 0] : __builtin_bit_cast(uint32x4_t, p0[idc[i]]);
 #pragma unroll
                     for (int d = 0; d < 4; ++d) add2_f16_f32(raw[i][d], b[d], v[i][2 * d], v[i][2 * d + 1]);
                 } else {
@@ -126,6 +144,9 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[i][e] = (OP == kOpGeluErf) ? gelu_erf(v[i][e]) : gelu_tanh(v[i][e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[i][e] = 0.0f;
             }
         }
     }
@@ -145,7 +166,7 @@ __global__ __launch_bounds__(256) void rowquant_kernel(const half8 *__restrict__
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
         const int idx = i * TPR + t;
-        if (idx < nvec) {
+        if (ok[i]) {
             if (y_out != nullptr) {
                 if (y_dtype == 1) {
                     float4 *yo = reinterpret_cast<float4 *>(reinterpret_cast<float *>(y_out) + (size_t)row * K) + 2 * idx;
