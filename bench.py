@@ -358,7 +358,7 @@ def time_gemm_a16(zq, name, M, reps_target=40):
     K, N, g, bits = zq_inputs.LINEARS[name]
     gen = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED % (2 ** 31) + 7 * M)
     wbytes = N * K
-    nset = int(max(1, min(32, -(-(640 << 20) // wbytes)))) if M <= 64 else 1
+    nset = int(max(1, min(32, -(-(640 << 20) // wbytes)))) if M <= 128 else 1
     x = (torch.randn((M, K), generator=gen, device="cuda") *
          torch.exp(torch.empty((M, 1), device="cuda").uniform_(np.log(0.5), np.log(2.0), generator=gen))).half()
     sets = []
@@ -369,7 +369,7 @@ def time_gemm_a16(zq, name, M, reps_target=40):
         sets.append((wq, sw))
     bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
     out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-    nws = zq.gemm_workspace_bytes(M, N, K, 8)
+    nws = zq.gemm_w8a16_workspace_bytes(M, N, K)
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
 
     def run(i):

@@ -215,11 +215,12 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
  *   x_fp16    in,  fp16 [M,K] row-major                      (device)
  *   wq        in,  int8 [N,K];  s_w  fp32 [groups];  bias_fp16  fp16 [N] or NULL   (device)
  *   out_fp16  out, fp16 [M,N]                                (device)
- *   workspace scratch of zq_gemm_workspace_bytes(M, N, K, 8) bytes or NULL: lets token counts up to
- *             64 split K across workgroups when the matrix has few rows (fp32 partials; the result
+ *   workspace scratch of zq_gemm_w8a16_workspace_bytes(M, N, K) bytes or NULL: lets token counts up to
+ *             128 split K across workgroups where that is faster (fp32 partials; the result
  *             does not depend on the order in which workgroups finish)
- * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (up to 64 tokens the streaming
- * schedule needs K % 256 == 0; other small shapes run an untiled schedule).  The codes are converted to
+ * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (up to 128 tokens the streaming
+ * schedule needs K % 256 == 0, and 65 to 128 tokens run as two launches of it over row halves; other
+ * small shapes run an untiled schedule).  The codes are converted to
  * FP16 exactly; the sum is accumulated in fp32 on the FP16 matrix cores, so unlike the INT8 calls
  * the result is reproducible but not bit-defined by the inputs alone (tolerance in the tests).
  * Calls that split K must not overlap with other GeMM calls on the same device.
@@ -228,6 +229,16 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
 zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
                                 const void *bias_fp16, int M, int N, int K, void *out_fp16, void *workspace,
                                 size_t workspace_bytes, zq_stream stream);
+
+/*
+ * Workspace that lets zq_gemm_w8a16_dequant split K for this shape (0: the call never splits, e.g.
+ * above 128 tokens), and the cut its streaming schedule takes for up to 64 tokens (arguments and
+ * results as zq_gemm_stream_plan; the cut is the INT8 call's unless that one divides strips into
+ * K ranges, which this schedule does not do).  Host-only; launch nothing.
+ */
+size_t zq_gemm_w8a16_workspace_bytes(int M, int N, int K);
+int zq_gemm_w8a16_stream_plan(int M, int N, int K, size_t workspace_bytes, int *row_blocks, int *k_splits,
+                              int *consumers);
 
 /*
  * Tuning and test hook: force the GeMM schedule instead of choosing it from

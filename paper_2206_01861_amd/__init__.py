@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     set_in_kernel_quant,
     gemm_stream_plan,
     gemm_stream_k_ranges,
+    gemm_w8a16_stream_plan,
+    gemm_w8a16_workspace_bytes,
     gemm_variant_name,
     gemm_workspace_bytes,
     force_gemm_variant,

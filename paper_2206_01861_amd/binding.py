@@ -17,7 +17,8 @@ SYMBOLS = [
     "zq_status_string", "zq_version", "zq_quantize_weight_groupwise", "zq_layernorm_quant_tokenwise",
     "zq_gelu_quant_tokenwise", "zq_gemm_workspace_bytes", "zq_gemm_i8_dequant", "zq_gemm_w4a8_dequant",
     "zq_debug_force_gemm_variant", "zq_gemm_variant_name", "zq_gemm_choose_variant", "zq_gemm_stream_plan", "zq_gemm_stream_k_ranges", "zq_gemm_gelu_quant_tokenwise", "zq_quantize_tokenwise", "zq_dequantize_acc",
-    "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant",
+    "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant", "zq_gemm_w8a16_workspace_bytes",
+    "zq_gemm_w8a16_stream_plan",
     "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
 ]
 
@@ -88,6 +89,10 @@ def lib():
     L.zq_gemm_stream_plan.restype = ci
     L.zq_gemm_stream_plan.argtypes = [ci, ci, ci, ci, sz] + [ctypes.POINTER(ci)] * 3
     L.zq_gemm_stream_k_ranges.restype = ci
+    L.zq_gemm_w8a16_workspace_bytes.restype = sz
+    L.zq_gemm_w8a16_workspace_bytes.argtypes = [ci, ci, ci]
+    L.zq_gemm_w8a16_stream_plan.restype = ci
+    L.zq_gemm_w8a16_stream_plan.argtypes = [ci, ci, ci, sz] + [ctypes.POINTER(ci)] * 3
     L.zq_gemm_stream_k_ranges.argtypes = [ci, ci, ci, ci, sz]
     _lib = L
     return L
@@ -169,6 +174,19 @@ def gemm_stream_plan(M, N, K, w_bits=8, workspace_bytes=0):
     rb, ks, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().zq_gemm_stream_plan(M, N, K, w_bits, workspace_bytes, ctypes.byref(rb), ctypes.byref(ks),
                                      ctypes.byref(c)))
+    return rb.value, ks.value, c.value
+
+
+def gemm_w8a16_workspace_bytes(M, N, K):
+    """Workspace that lets zq_gemm_w8a16_dequant split K for this shape (0: it never splits)."""
+    return lib().zq_gemm_w8a16_workspace_bytes(M, N, K)
+
+
+def gemm_w8a16_stream_plan(M, N, K, workspace_bytes=0):
+    """(row_blocks, k_splits, consumers) of the W8A16 streaming schedule (up to 64 tokens)."""
+    rb, ks, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().zq_gemm_w8a16_stream_plan(M, N, K, workspace_bytes, ctypes.byref(rb), ctypes.byref(ks),
+                                           ctypes.byref(c)))
     return rb.value, ks.value, c.value
 
 

@@ -190,6 +190,24 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
                        workspace_bytes, w_bits, approx_tanh ? 2 : 1, true, stream);
 }
 
+namespace {
+constexpr int kA16StreamTokens = 128;   // FP16 activations: weight streaming up to here, in launches of 64 tokens
+}
+
+size_t zq_gemm_w8a16_workspace_bytes(int M, int N, int K) {
+    if (M <= 0 || N <= 0 || K <= 0 || (N % 16) != 0 || (K % 256) != 0 || M > kA16StreamTokens) return 0;
+    return zq::stream_a16_workspace_bytes(M < 64 ? M : 64, N, K);
+}
+
+int zq_gemm_w8a16_stream_plan(int M, int N, int K, size_t workspace_bytes, int *row_blocks, int *k_splits,
+                              int *consumers) {
+    if (row_blocks == nullptr || k_splits == nullptr || consumers == nullptr) return ZQ_ERR_NULL;
+    if (M <= 0 || M > 64 || N <= 0 || (N % 16) != 0 || K <= 0 || (K % 256) != 0) return ZQ_ERR_UNSUPPORTED;
+    const size_t need = zq::stream_a16_workspace_bytes(M, N, K);
+    zq::stream_a16_plan(M, N, K, need > 0 && workspace_bytes >= need, row_blocks, k_splits, consumers);
+    return ZQ_OK;
+}
+
 zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
                                 const void *bias_fp16, int M, int N, int K, void *out_fp16, void *workspace,
                                 size_t workspace_bytes, zq_stream stream) {
@@ -207,10 +225,19 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
     a.M = M; a.N = N; a.K = K; a.out = out_fp16; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     hipError_t e;
-    if (M <= 64 && (K % 256) == 0) {
-        // the K split is taken only when the workspace holds its fp32 partials (same size as the INT8 call's)
-        const size_t need = zq::gemm_variant_workspace(zq::kGemmSkinnySplitK, M, N, K, 8);
-        e = zq::launch_gemm_a16_stream(a, need > 0 && workspace_bytes >= need, st);
+    if (M <= kA16StreamTokens && (K % 256) == 0) {
+        // Weight streaming holds up to 64 tokens per launch; 65..128 tokens run as two launches over
+        // row halves (the weights are read twice, which is still well ahead of the tiled schedule on
+        // so few rows).  The K split is taken only when the workspace holds its fp32 partials.
+        e = hipSuccess;
+        for (int m0 = 0; m0 < M && e == hipSuccess; m0 += 64) {
+            zq::A16Args h = a;
+            h.M = (M - m0) < 64 ? (M - m0) : 64;
+            h.x = static_cast<const uint16_t *>(x_fp16) + (size_t)m0 * K;
+            h.out = static_cast<uint16_t *>(out_fp16) + (size_t)m0 * N;
+            const size_t need = zq::stream_a16_workspace_bytes(h.M, N, K);
+            e = zq::launch_gemm_a16_stream(h, need > 0 && workspace_bytes >= need, st);
+        }
     } else if ((long)M * N * K > (1L << 27)) {
         e = zq::launch_gemm_a16_tile(a, st);
     } else {

@@ -845,13 +845,37 @@ hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStre
 }
 }  // namespace
 
-// FP16 activations: the same cut as the INT8 call of the same shape (the weight stream is the same).
+// FP16 activations: the cut of the INT8 call of the same shape (the weight stream is the same), without
+// K ranges, which this kernel does not have.  (Weighting the activation tile twice, as its bytes
+// would suggest, made the model pick cuts that measured slower; measured better cuts for single
+// shapes, e.g. a four-way K split of 4096x4096 at 32 to 64 tokens, can be entered in the schedule table.)
+namespace {
+StreamPlan plan_stream_a16(int M, int N, int K, bool allow_split) {
+    return plan_stream(M, N, K, 8, allow_split, false);
+}
+}  // namespace
+
+// Workspace of the K-split schedule for FP16 activations: one fp32 partial of M x N per split.
+size_t stream_a16_workspace_bytes(int M, int N, int K) {
+    if (K / kStageK < 1) return 0;
+    const StreamPlan plan = plan_stream_a16(M, N, K, true);
+    if (plan.k_splits <= 1) return 0;
+    return (size_t)plan.k_splits * M * N * sizeof(float);
+}
+
+void stream_a16_plan(int M, int N, int K, bool allow_split, int *row_blocks, int *k_splits, int *consumers) {
+    const StreamPlan plan = plan_stream_a16(M, N, K, allow_split);
+    *row_blocks = plan.row_blocks;
+    *k_splits = plan.k_splits;
+    *consumers = plan.consumers;
+}
+
 hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st) {
-    StreamPlan plan = plan_stream(a.M, a.N, a.K, 8, allow_split, false);   // this kernel has no K ranges
-    // Without ranges the planner may want more K splits than the INT8 call whose workspace size the
-    // caller was told: never split further than the workspace holds.
+    StreamPlan plan = plan_stream_a16(a.M, a.N, a.K, allow_split);
+    // never split further than the workspace holds (a schedule-table entry may ask for more splits
+    // than the size the caller was told)
     if (plan.k_splits > 1 && (size_t)plan.k_splits * a.M * a.N * sizeof(float) > a.workspace_bytes)
-        plan = plan_stream(a.M, a.N, a.K, 8, false, false);
+        plan = plan_stream_a16(a.M, a.N, a.K, false);
     const int mt = token_tiles(a.M);
     if (mt <= 1) return launch_stream_a16_t<1>(a, plan, st);
     if (mt <= 2) return launch_stream_a16_t<2>(a, plan, st);

@@ -83,11 +83,13 @@ struct A16Args {
     const void *bias;     // fp16 [N] or null
     int M, N, K;
     void *out;            // fp16 [M,N]
-    void *workspace;      // fp32 partials of the K split (same size as the INT8 call's workspace)
+    void *workspace;      // fp32 partials of the K split
     size_t workspace_bytes;
 };
 hipError_t launch_gemm_a16_simple(const A16Args &a, hipStream_t st);
 hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_t st);   // M <= 64, K % 256 == 0
+size_t stream_a16_workspace_bytes(int M, int N, int K);                                   // of that schedule's K split
+void stream_a16_plan(int M, int N, int K, bool allow_split, int *row_blocks, int *k_splits, int *consumers);
 hipError_t launch_gemm_a16_tile(const A16Args &a, hipStream_t st);                       // any K the ABI accepts
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);

@@ -272,6 +272,22 @@ def test_w8a16_validation():
     assert call(ws=P + 4, ws_bytes=64) == E_ALIGN
 
 
+def test_w8a16_workspace_and_plan():
+    """The W8A16 call's own workspace query: the size of the fp32 partials of the cut it would take
+    (for 65 to 128 tokens, of its 64-token launches), 0 where it never splits; the plan covers the matrix."""
+    for (M, N, K) in [(1, 2048, 8192), (32, 2048, 8192), (64, 6144, 24576), (16, 12288, 4096), (64, 4112, 16384)]:
+        ws = zq.gemm_w8a16_workspace_bytes(M, N, K)
+        rb, ks, c = zq.gemm_w8a16_stream_plan(M, N, K, ws)
+        assert 1 <= rb <= N // 16 and 1 <= c <= 8 and c == -(-(N // 16) // rb)
+        assert ws == (ks * M * N * 4 if ks > 1 else 0)
+        assert zq.gemm_w8a16_stream_plan(M, N, K, 0)[1] == 1
+    assert zq.gemm_w8a16_workspace_bytes(100, 2048, 8192) == zq.gemm_w8a16_workspace_bytes(64, 2048, 8192) > 0
+    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) == 0      # tiled above 128 tokens
+    assert zq.gemm_w8a16_workspace_bytes(16, 2048, 1000) == 0       # K not a multiple of 256: untiled
+    with pytest.raises(zq.ZQError):
+        zq.gemm_w8a16_stream_plan(65, 2048, 8192)
+
+
 def test_missing_library_is_an_error(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libzq.so"))

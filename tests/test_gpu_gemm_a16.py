@@ -30,8 +30,8 @@ def _check(orc, out16, x, codes, s_w, bias, what, rows=None):
 
 
 SHAPES = [
-    # (M, N, K, groups): the untiled schedule (ragged K, M > 64) ...
-    (1, 16, 16, 1), (17, 768, 784, 48), (129, 96, 1024, 2), (70, 272, 256, 17),
+    # (M, N, K, groups): the untiled schedule (ragged K, M > 128) ...
+    (1, 16, 16, 1), (17, 768, 784, 48), (129, 96, 1024, 2), (70, 272, 208, 17),
     # ... the streaming schedule, one to four token tiles, uneven strips ...
     (1, 64, 256, 4), (8, 6144, 2048, 128), (33, 144, 1792, 9), (64, 1024, 1536, 64), (16, 33040, 512, 5),
     (50, 16, 256, 1),
@@ -40,6 +40,8 @@ SHAPES = [
     (515, 1024, 400, 64), (300, 1040, 1008, 65),       # K not a multiple of the stage depth
     # ... and with a K split
     (32, 2048, 8192, 128), (7, 528, 24576, 11), (64, 4112, 16384, 1), (1, 2048, 8192, 128),
+    # 65 to 128 tokens: two streaming launches over row halves (second half ragged, one row, full), also with a K split
+    (65, 1024, 1536, 64), (100, 6144, 2048, 128), (128, 2064, 512, 3), (90, 2048, 8192, 128), (128, 528, 24576, 11),
 ]
 
 
@@ -51,7 +53,7 @@ def test_w8a16_against_oracle(zq, orc, M, N, K, g):
     codes = zq_inputs.random_codes(rng, (N, K))
     s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-2)
     bias = zq_inputs.bias(rng, N)
-    nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
+    nbytes = zq.gemm_w8a16_workspace_bytes(M, N, K)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
     out = zq.zq_gemm_w8a16_dequant(dev(x), dev(codes), dev(s_w), dev(bias), workspace=ws)
     out2 = zq.zq_gemm_w8a16_dequant(dev(x), dev(codes), dev(s_w), dev(bias), workspace=ws)
@@ -80,7 +82,7 @@ def test_w8a16_integer_inputs_are_exact(zq, orc):
     assert np.array_equal(host(out).view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("name,M", [("c5_qkv", 64), ("c4_qkv", 16), ("c3_qkv", 1), ("c3_qkv", 2048), ("c4_qkv", 4096)])
+@pytest.mark.parametrize("name,M", [("c5_qkv", 64), ("c4_qkv", 16), ("c4_qkv", 128), ("c3_qkv", 1), ("c3_qkv", 2048), ("c4_qkv", 4096)])
 def test_w8a16_full_size_sampled_rows(zq, orc, name, M):
     """QKV linears at workload size in the launch configuration the benchmark times; sampled rows."""
     K, N, g, bits = zq_inputs.LINEARS[name]
@@ -90,7 +92,7 @@ def test_w8a16_full_size_sampled_rows(zq, orc, name, M):
     codes = torch.randint(-127, 128, (N, K), generator=gen, device="cuda", dtype=torch.int8)
     s_w = (torch.rand(g, generator=gen, device="cuda") * 1e-3 + 1e-4)
     bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
-    nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
+    nbytes = zq.gemm_w8a16_workspace_bytes(M, N, K)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
     out = zq.zq_gemm_w8a16_dequant(x, codes, s_w, bias, workspace=ws)
     torch.cuda.synchronize()
