@@ -219,7 +219,7 @@ def test_quantized_linear_end_to_end(zq, orc):
 # Full-size workloads: sampled rows against the oracle plus the Freivalds identity on everything.
 FULL = [
     ("c2_ffc1", 4096), ("c2_ffc2", 4096), ("c3_qkv", 2048), ("c3_ffc2", 32), ("c3_ffc1", 1),
-    ("c4_ffc1", 16), ("c4_ffc2", 1), ("c4_ffc1", 4096), ("c4_qkv", 16), ("c5_ffc2", 64), ("c5_qkv", 64),
+    ("c4_ffc1", 16), ("c4_ffc2", 1), ("c4_ffc1", 4096), ("c4_qkv", 16), ("c4_out", 1), ("c5_ffc2", 64), ("c5_qkv", 64),
     ("c5_ffc1", 16384),
 ]
 
