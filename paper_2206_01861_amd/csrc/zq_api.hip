@@ -194,9 +194,23 @@ namespace {
 constexpr int kA16StreamTokens = 128;   // FP16 activations: weight streaming up to here, in launches of 64 tokens
 }
 
+// 65 to 128 tokens: the tiled schedule with a K split where it divides K at least three ways (measured
+// ahead of two streaming launches there: 4096x4096 at 128 tokens 32.5 -> 21 us), else streaming.
+static bool a16_tiles_with_split(int M, int N, int K) {
+    if (M <= 64) return false;
+    const int ks = zq::gemm_a16_tile_splits(M, N, K);
+    return ks >= ((M <= kA16StreamTokens && (K % 256) == 0) ? 3 : 2);
+}
+
 size_t zq_gemm_w8a16_workspace_bytes(int M, int N, int K) {
-    if (M <= 0 || N <= 0 || K <= 0 || (N % 16) != 0 || (K % 256) != 0 || M > kA16StreamTokens) return 0;
-    return zq::stream_a16_workspace_bytes(M < 64 ? M : 64, N, K);
+    if (M <= 0 || N <= 0 || K <= 0 || (N % 16) != 0 || (K % 16) != 0) return 0;
+    size_t need = 0;
+    if (M <= kA16StreamTokens && (K % 256) == 0) need = zq::stream_a16_workspace_bytes(M < 64 ? M : 64, N, K);
+    if (a16_tiles_with_split(M, N, K)) {
+        const size_t t = zq::gemm_a16_tile_split_workspace(M, N, K);
+        if (t > need) need = t;
+    }
+    return need;
 }
 
 int zq_gemm_w8a16_stream_plan(int M, int N, int K, size_t workspace_bytes, int *row_blocks, int *k_splits,
@@ -225,7 +239,11 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
     a.M = M; a.N = N; a.K = K; a.out = out_fp16; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     hipError_t e;
-    if (M <= kA16StreamTokens && (K % 256) == 0) {
+    const bool tile_split = a16_tiles_with_split(M, N, K) &&
+                            workspace_bytes >= zq::gemm_a16_tile_split_workspace(M, N, K);
+    if (tile_split) {
+        e = zq::launch_gemm_a16_tile(a, st);
+    } else if (M <= kA16StreamTokens && (K % 256) == 0) {
         // Weight streaming holds up to 64 tokens per launch; 65..128 tokens run as two launches over
         // row halves (the weights are read twice, which is still well ahead of the tiled schedule on
         // so few rows).  The K split is taken only when the workspace holds its fp32 partials.
@@ -277,6 +295,7 @@ const char *zq_gemm_variant_name(int variant) {
         case zq::kGemmSkinnySplitK: return "skinny_splitk";
         case zq::kGemmTile256x128: return "tile256x128";
         case zq::kGemmTile256x192: return "tile256x192";
+        case zq::kGemmTileSplitK: return "tile128_splitk";
     }
     return nullptr;
 }

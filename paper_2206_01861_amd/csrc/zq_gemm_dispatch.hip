@@ -49,6 +49,7 @@ bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_
 }
 
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits) {
+    if (variant == kGemmTileSplitK) return gemm_tile_split_workspace(M, N, K);
     if (variant != kGemmSkinnySplitK || M > kStreamMaxTokens || (K % 256) != 0) return 0;
     return stream_workspace_bytes(M, N, K, w_bits);
 }
@@ -62,6 +63,8 @@ bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t 
         case kGemmTile256x128:
         case kGemmTile256x192:
             return true;                              // the last stage of a ragged K is zero filled
+        case kGemmTileSplitK:
+            return gemm_tile_splits(M, N, K) > 1 && workspace_bytes >= gemm_tile_split_workspace(M, N, K);
         case kGemmSkinny:
             return M <= kStreamMaxTokens && (K % 256) == 0;
         case kGemmSkinnySplitK:
@@ -78,6 +81,7 @@ hipError_t launch_gemm(int variant, const GemmArgs &a, hipStream_t st) {
         case kGemmTile256: return launch_gemm_tile(a, 256, st);
         case kGemmTile256x128: return launch_gemm_tile(a, 192, st);
         case kGemmTile256x192: return launch_gemm_tile(a, 256192, st);
+        case kGemmTileSplitK: return launch_gemm_tile_splitk(a, st);
         case kGemmSkinny: return launch_gemm_skinny(a, false, st);
         case kGemmSkinnySplitK: return launch_gemm_skinny(a, true, st);
     }
@@ -104,6 +108,9 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
     // Tiny problems (a BERT-base layer at 128 tokens) are all latency: one wave per 16x16 tile straight
     // from global memory starts and finishes sooner than a handful of LDS-tiled workgroups (6.2 vs 6.8 us).
     if ((long)M * N * K <= (1L << 27)) return kGemmSimple;
+    // Few tiles against a long K (some hundred tokens, a few thousand columns): split K over the idle
+    // compute units when the caller's workspace holds the partial products.
+    if (gemm_variant_supports(kGemmTileSplitK, M, N, K, w_bits, workspace_bytes)) return kGemmTileSplitK;
     // Tiled schedules.  The tiles of a launch all take the same time and a compute unit holds one of
     // them (two of the four-wave 128x128 ones), so a launch lasts (rounds of tiles) x (time of a
     // tile), and the time of a tile goes with its area times a factor for the operand bytes it moves

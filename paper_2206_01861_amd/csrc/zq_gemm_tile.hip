@@ -90,12 +90,16 @@ struct TileCfg {
 }  // namespace
 
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0>
+// KSPLIT = 1: the launch holds k_splits workgroups per tile, each multiplies its own range of K stages
+// and writes the raw accumulators of its tile to partial[split][M][N] (INT32, or fp32 bits with
+// XT = 1); a second kernel adds the splits and applies the epilogue (splitk_finish_kernel below).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0,
+          int KSPLIT = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
     half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act,
-    int8_t *__restrict__ q_out, float *__restrict__ q_scale_out) {
+    int8_t *__restrict__ q_out, float *__restrict__ q_scale_out, int k_splits, int32_t *__restrict__ partial) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -117,6 +121,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr int XB = (XT == 1) ? 2 : 1;            // bytes per activation value
     static_assert(XT == 0 || WBITS == 8, "FP16 activations go with INT8 weights");
     static_assert(QOUT == 0 || XT == 0, "the output quantization is built for the INT8 product");
+    static_assert(KSPLIT == 0 || QOUT == 0, "a K split leaves the epilogue to the second kernel");
     constexpr int DIRECT_UNITS = STAGED_W ? XU : (XU + WU);
     static_assert(XU % NW == 0 && WU % NW == 0, "load units must split evenly over the waves");
     using AccT = typename std::conditional<XT == 1, float32x16, int32x16>::type;
@@ -134,7 +139,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // unfinished band always has all its tiles running.  (Round-robin over the XCDs still gives each
     // XCD a fixed set of weight column tiles.)
     int tm, tn;
-    if constexpr (QOUT == 1) {
+    int split = 0;                                   // KSPLIT: which range of K stages this workgroup takes
+    if constexpr (KSPLIT == 1) {
+        split = blockIdx.x % k_splits;               // the splits of a tile have consecutive ids
+        const int t = blockIdx.x / k_splits;
+        tm = t / tiles_n;
+        tn = t % tiles_n;
+    } else if constexpr (QOUT == 1) {
         tm = blockIdx.x / tiles_n;
         tn = blockIdx.x % tiles_n;
     } else {
@@ -205,6 +216,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     }
 
     const int nkt = (xrow_bytes + BK - 1) / BK;
+    // stages kt0 .. kt0 + n_loc - 1 are this workgroup's; all of them without a K split
+    int kt0 = 0, n_loc = nkt;
+    if constexpr (KSPLIT == 1) {
+        const int base = nkt / k_splits, rem = nkt % k_splits;   // the launcher keeps k_splits <= nkt
+        kt0 = split * base + (split < rem ? split : rem);
+        n_loc = base + (split < rem ? 1 : 0);
+    }
     auto issue_direct = [&](int kt, int slot) {
         uint8_t *base = smem + slot * STAGE;
         const bool last = kt == nkt - 1;
@@ -316,10 +334,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     int32x4 a0[FN], b0[FM], a1[FN], b1[FM];
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
-        if (s < nkt) {
-            issue_direct(s, s);
+        if (s < n_loc) {
+            issue_direct(kt0 + s, s);
             if (STAGED_W) {
-                w4_fetch(s);
+                w4_fetch(kt0 + s);
                 w4_store(s);
             }
         }
@@ -330,7 +348,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // any of them is used, so that their round trip runs under the operand loads instead of in
     // front of them (it used to cost three dependent round trips before the first operand load).
     static_assert(BN <= NT && BM <= NT, "one scale element per thread");
-    {
+    if constexpr (KSPLIT == 0) {
         const int c = threadIdx.x;
         int n = n0 + (c < BN ? c : 0);
         if (n > N - 1) n = N - 1;
@@ -346,14 +364,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         }
         if (c < BM) row_scale[c] = st_v;
     }
-    if (!STAGED_W && nkt >= NSTAGE)
+    if (!STAGED_W && n_loc >= NSTAGE)
         wait_vmcnt<(NSTAGE - 1) * LPS>();      // stage 0 has landed; later stages may still be in flight
     else
         wait_vmcnt<0>();
     __syncthreads();
     read_frags(smem, 0, a0, b0);
 
-    for (int kt = 0; kt < nkt; ++kt) {
+    for (int kt = 0; kt < n_loc; ++kt) {       // kt counts this workgroup's stages; kt0 + kt is the stage of K
         const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
         const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
 #pragma unroll
@@ -366,18 +384,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 read_frags(sb, ks + 1, na, nb2);
                 mfma_step(ca, cb);
                 interleave();
-                if (STAGED_W && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < nkt)
+                if (STAGED_W && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < n_loc)
                     w4_store((kt + NSTAGE - 1) % NSTAGE);     // registers fetched at the previous stage boundary
             } else {
-                if (kt + 1 < nkt) {
-                    if (!STAGED_W && kt + NSTAGE - 1 < nkt)
+                if (kt + 1 < n_loc) {
+                    if (!STAGED_W && kt + NSTAGE - 1 < n_loc)
                         wait_vmcnt<(NSTAGE - 2) * LPS>();     // stage kt+1 has landed
                     else
                         wait_vmcnt<0>();
                     lds_barrier();
-                    if (kt + NSTAGE < nkt) {
-                        issue_direct(kt + NSTAGE, kt % NSTAGE);
-                        if (STAGED_W) w4_fetch(kt + NSTAGE);
+                    if (kt + NSTAGE < n_loc) {
+                        issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE);
+                        if (STAGED_W) w4_fetch(kt0 + kt + NSTAGE);
                     }
                     read_frags(sn, 0, na, nb2);
                 }
@@ -389,6 +407,46 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // ---- epilogue ---------------------------------------------------------
     // acc[fn][fm][v]: output column n = wn*WN + fn*32 + 8*(v/4) + 4*(lane/32) + v%4,
     //                 token row     m = wm*WM + fm*32 + lane%32.
+    if constexpr (KSPLIT == 1) {
+        // K split: the raw accumulators of this range of K go to partial[split][M][N]; the second
+        // kernel adds the splits in order and applies scales, bias and activation.  Each wave turns its
+        // WM x WN block through a wave-private LDS buffer (rows padded by 16 bytes against bank
+        // conflicts; the LDS operations of one wave complete in order) so that it leaves as whole row
+        // segments of WN * 4 bytes instead of one 16-byte piece per row and lane.
+        constexpr int PROW = WN + 4;                  // ints per padded row
+        static_assert(NW * WM * PROW * 4 <= NSTAGE * STAGE, "the partial tile is staged in the stage ring");
+        static_assert((WM * WN / 4) % 64 == 0, "whole store instructions per wave");
+        __syncthreads();                              // all reads of the last stage are done
+        int32_t *pt = reinterpret_cast<int32_t *>(smem) + wave * (WM * PROW);
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if constexpr (XT == 1)
+                            v[e] = __float_as_int(acc[fn][fm][4 * q + e]);
+                        else
+                            v[e] = acc[fn][fm][4 * q + e];
+                    }
+                    *reinterpret_cast<int32x4 *>(pt + (fm * 32 + lr) * PROW + fn * 32 + 8 * q + 4 * lc) = v;
+                }
+            }
+        }
+        int32_t *mine = partial + (size_t)split * M * N;
+        constexpr int CPW = WN / 4;                   // 16-byte pieces per row of the wave's block
+#pragma unroll
+        for (int i = 0; i < WM * CPW / 64; ++i) {
+            const int row = (i * 64 + lane) / CPW, c = (i * 64 + lane) % CPW;
+            const int32x4 v = *reinterpret_cast<const int32x4 *>(pt + row * PROW + c * 4);
+            const int m = m0 + wm * WM + row, n = n0 + wn * WN + c * 4;
+            if (m < M && n < N) *reinterpret_cast<int32x4 *>(mine + (size_t)m * N + n) = v;
+        }
+        return;
+    }
     __syncthreads();                          // all reads of the last stage are done; LDS is reused below
     constexpr int OROW = Cfg::kEpiRow;
     uint8_t *ot = smem + wave * (32 * OROW);  // wave-private: 32 rows of this wave's columns
@@ -569,21 +627,102 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 
 namespace {
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0>
-hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0,
+          int KSPLIT = 0>
+hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st, int k_splits = 1) {
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     constexpr size_t lds = QOUT ? Cfg::kLdsQ : Cfg::kLds;
     static std::atomic<uint64_t> configured{0};
-    const void *kernel =
-        reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT>);
+    const void *kernel = reinterpret_cast<const void *>(
+        &gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT>),
-                       dim3(tiles_m * tiles_n), dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok,
+    if (KSPLIT == 0 && k_splits != 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT>),
+                       dim3(tiles_m * tiles_n * k_splits), dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok,
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
-                       a.acc_out, tiles_m, tiles_n, a.act, a.q_out, a.q_scale_out);
+                       a.acc_out, tiles_m, tiles_n, a.act, a.q_out, a.q_scale_out, k_splits,
+                       reinterpret_cast<int32_t *>(a.workspace));
     return hipGetLastError();
+}
+
+// Second kernel of the K split: adds the partial products of the splits (in split order, so that the
+// fp32 sums of the FP16-activation product do not depend on timing) and applies the epilogue of the
+// tiled kernel: acc * (s_tok[row] * s_w[group]) + bias, activation, one rounding to FP16.  One thread
+// per four consecutive columns; INT4 products carry the factor 16 of the nibble unpack until here.
+template <int XT>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const int32x4 *__restrict__ partial, int k_splits,
+                                                            const float *__restrict__ s_tok,
+                                                            const float *__restrict__ s_w, int gs,
+                                                            const half_t *__restrict__ bias, int M, int N,
+                                                            half4 *__restrict__ out, int32x4 *__restrict__ acc_out,
+                                                            int act, int shift) {
+    const int nq = N >> 2;
+    const long total = (long)M * nq;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int m = (int)(i / nq);
+        const int n = (int)(i - (long)m * nq) * 4;
+        float fv[4];
+        int32x4 sum = {0, 0, 0, 0};
+        if constexpr (XT == 1) {
+            float32x4 fs = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+            for (int s = 0; s < k_splits; ++s) fs += __builtin_bit_cast(float32x4, partial[(long)s * total + i]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) fv[e] = fs[e];
+        } else {
+#pragma unroll 4
+            for (int s = 0; s < k_splits; ++s) sum += partial[(long)s * total + i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sum[e] >>= shift;                     // exact: every INT4 product carried the factor 16
+                fv[e] = (float)sum[e];
+            }
+            if (acc_out != nullptr) acc_out[i] = sum;
+        }
+        const float st = (XT == 1) ? 1.0f : s_tok[m];
+        const float sc = s_w[n / gs];
+        float f[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float cb = (bias != nullptr) ? (float)bias[n + e] : 0.0f;
+            f[e] = fv[e] * (st * sc) + cb;
+        }
+        apply_activation_n<4>(f, act);
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
+        out[i] = o;
+    }
+}
+
+// K splits of the 128x128-tile schedule for a shape whose tiles leave most compute units idle: at
+// most as many as fill the chip once, at least four stages of K each, at most sixteen, and among
+// those the count with the lowest modelled time; 1 = no split pays.  The model, fitted to
+// measurements at 130 to 1024 tokens (microseconds): a tile over K takes 4.5 + u per 1024 bytes of
+// an activation row (u = 4.0 for INT8 activations, 5.2 for FP16 ones); the K split adds the second
+// kernel's launch, 3, and 0.5 per MB of partial products written and read back.
+int tile_splits(int M, int N, int K, int x_bytes) {
+    const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+    const int nkt = (K * x_bytes + 127) / 128;
+    if (tiles > 128 || nkt < 8) return 1;
+    int ks_max = (int)(256 / tiles);
+    if (ks_max > nkt / 4) ks_max = nkt / 4;
+    if (ks_max > 16) ks_max = 16;
+    const double unit = (x_bytes == 1) ? 4.0 : 5.2;
+    const double k_units = (double)K * x_bytes / 1024.0;
+    const double whole = 4.5 + unit * k_units;
+    int best = 1;
+    double best_t = 0.9 * whole;                      // a split has to win by a tenth
+    for (int ks = 2; ks <= ks_max; ++ks) {
+        const double t = 7.5 + unit * k_units / ks + 0.5e-6 * ks * (double)M * N * 4.0;
+        if (t < best_t) {
+            best_t = t;
+            best = ks;
+        }
+    }
+    return best;
 }
 
 // Tile edge of the schedule that quantizes its output in the kernel: 256 where the plain call
@@ -623,6 +762,43 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
 }
 
+// The 128x128-tile schedule with K split over workgroups and a second kernel for the epilogue: for
+// token counts above the streaming schedules' whose tiles would occupy less than half the chip.
+// a.workspace holds the partial products, tile_split_workspace() bytes.
+int gemm_tile_splits(int M, int N, int K) {
+    if (M <= 128 && (K % 256) == 0) return 1;        // the streaming schedules take these
+    return tile_splits(M, N, K, 1);
+}
+
+size_t gemm_tile_split_workspace(int M, int N, int K) {
+    const int ks = gemm_tile_splits(M, N, K);
+    return ks > 1 ? (size_t)ks * M * N * sizeof(int32_t) : 0;
+}
+
+namespace {
+template <int XT>
+hipError_t launch_splitk_finish(const GemmArgs &a, int k_splits, hipStream_t st) {
+    const long total = (long)a.M * (a.N / 4);
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL((splitk_finish_kernel<XT>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       reinterpret_cast<const int32x4 *>(a.workspace), k_splits, a.s_tok, a.s_w, a.N / a.groups,
+                       reinterpret_cast<const half_t *>(a.bias), a.M, a.N, reinterpret_cast<half4 *>(a.out),
+                       reinterpret_cast<int32x4 *>(a.acc_out), a.act, a.w_bits == 4 ? 4 : 0);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st) {
+    const int ks = gemm_tile_splits(a.M, a.N, a.K);
+    if (ks < 2 || a.workspace == nullptr || a.workspace_bytes < (size_t)ks * a.M * a.N * sizeof(int32_t))
+        return hipErrorInvalidValue;
+    hipError_t e = (a.w_bits == 8) ? launch_tile_t<128, 128, 2, 4, 128, 4, 8, 0, 0, 1>(a, st, ks)
+                                   : launch_tile_t<128, 128, 2, 4, 128, 4, 4, 0, 0, 1>(a, st, ks);
+    if (e != hipSuccess) return e;
+    return launch_splitk_finish<0>(a, ks, st);
+}
+
 // The tiled GeMM with the token-wise quantization of its output inside the kernel (a.q_out,
 // a.q_scale_out; a.out optional).  The tiles of a band of token rows wait for each other, so a band
 // must fit on the chip several times over, and every (tile, row) needs a slot of the exchange array.
@@ -652,6 +828,14 @@ hipError_t quant_wait_expired(unsigned *count) {
     return hipMemcpyToSymbol(HIP_SYMBOL(g_quant_wait_expired), &zero, sizeof(unsigned));
 }
 
+// K splits of the FP16-activation call on the tiled schedule (1: none) and the workspace they need.
+int gemm_a16_tile_splits(int M, int N, int K) { return tile_splits(M, N, K, 2); }
+
+size_t gemm_a16_tile_split_workspace(int M, int N, int K) {
+    const int ks = tile_splits(M, N, K, 2);
+    return ks > 1 ? (size_t)ks * M * N * sizeof(float) : 0;
+}
+
 // FP16 activations x INT8 weights on the tiled schedules.  The argument block is the
 // INT8 one with xq pointing at the FP16 activations and no token scales.
 hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
@@ -660,7 +844,13 @@ hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
     a.s_tok = nullptr;
     a.wq = a16.wq; a.s_w = a16.s_w; a.groups = a16.groups; a.bias = a16.bias;
     a.M = a16.M; a.N = a16.N; a.K = a16.K; a.out = a16.out; a.acc_out = nullptr;
-    a.workspace = nullptr; a.workspace_bytes = 0; a.w_bits = 8; a.act = 0;
+    a.workspace = a16.workspace; a.workspace_bytes = a16.workspace_bytes; a.w_bits = 8; a.act = 0;
+    // few tiles against a long K: split K (fp32 partials, added in split order by the second kernel)
+    const int ks = tile_splits(a.M, a.N, a.K, 2);
+    if (ks > 1 && a.workspace != nullptr && a.workspace_bytes >= (size_t)ks * a.M * a.N * sizeof(float)) {
+        if (hipError_t e = launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1, 0, 1>(a, st, ks); e != hipSuccess) return e;
+        return launch_splitk_finish<1>(a, ks, st);
+    }
     // the tile is chosen like the INT8 call's: rounds of tiles x area x a factor per tile shape
     const long rows256 = (a.M + 255) / 256;
     auto rounds = [](long tiles) { return (tiles + 255) / 256; };

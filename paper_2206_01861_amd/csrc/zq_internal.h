@@ -45,7 +45,8 @@ enum GemmVariant {
     kGemmSkinnySplitK = 4,// same, K also split across workgroups (needs workspace)
     kGemmTile256x128 = 5, // 256x128 block tile, four waves, two workgroups per CU
     kGemmTile256x192 = 6, // 256x192 block tile, eight waves: for grids that 256x256 tiles fill badly
-    kGemmVariantCount = 7
+    kGemmTileSplitK = 7,  // 128x128 block tile, K split over workgroups, epilogue in a second kernel (needs workspace)
+    kGemmVariantCount = 8
 };
 
 struct GemmArgs {
@@ -65,6 +66,12 @@ struct GemmArgs {
     int8_t *q_out = nullptr;       // launch_gemm_tile_quant: int8 [M,N] codes of the output rows
     float *q_scale_out = nullptr;  //                         fp32 [M] their scales
 };
+
+// 128x128 tiles with a K split: how many splits pay for a shape (1 = none), the workspace they
+// need, and the launch (two kernels).
+int gemm_tile_splits(int M, int N, int K);
+size_t gemm_tile_split_workspace(int M, int N, int K);
+hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st);
 
 // Tiled GeMM that also quantizes its output rows token-wise inside the kernel (out may be null).
 bool gemm_tile_quant_supported(int M, int N);
@@ -91,6 +98,8 @@ hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_
 size_t stream_a16_workspace_bytes(int M, int N, int K);                                   // of that schedule's K split
 void stream_a16_plan(int M, int N, int K, bool allow_split, int *row_blocks, int *k_splits, int *consumers);
 hipError_t launch_gemm_a16_tile(const A16Args &a, hipStream_t st);                       // any K the ABI accepts
+int gemm_a16_tile_splits(int M, int N, int K);                                          // K splits that pay on tiles, 1 = none
+size_t gemm_a16_tile_split_workspace(int M, int N, int K);                              // of its K split, 0 if none
 
 bool gemm_variant_supports(int variant, int M, int N, int K, int w_bits, size_t workspace_bytes);
 size_t gemm_variant_workspace(int variant, int M, int N, int K, int w_bits);

@@ -255,6 +255,20 @@ def test_tuning_table_overrides_the_choice():
     assert zq.tune_count() == 0 and zq.gemm_choose_variant(16, 4096, 4096, 8, 0) == base
 
 
+def test_tile_k_split_dispatch():
+    """Above the streaming schedules' token counts, a shape whose 128x128 tiles would occupy less than
+    half the chip splits K when the workspace holds the partial products, and only then."""
+    for (M, N, K) in [(192, 4096, 4096), (300, 2048, 8192), (130, 4096, 4000), (96, 1040, 3968)]:
+        ws = zq.gemm_workspace_bytes(M, N, K, 8)
+        assert ws > 0 and ws % (M * N * 4) == 0 and 2 <= ws // (M * N * 4) <= 16
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws)) == "tile128_splitk"
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws - 1)) != "tile128_splitk"
+        assert zq.gemm_workspace_bytes(M, N, K, 4) == ws            # the INT4 call splits alike
+    for (M, N, K) in [(1024, 4096, 4096), (384, 4096, 4096), (256, 4096, 1024), (4096, 4096, 1024), (129, 12288, 4096)]:
+        assert zq.gemm_workspace_bytes(M, N, K, 8) == 0             # enough tiles, or K too short to pay
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(100, 4096, 4096, 8, 1 << 30)) == "skinny"
+
+
 def test_w8a16_validation():
     f = zq.lib().zq_gemm_w8a16_dequant
 
@@ -281,8 +295,14 @@ def test_w8a16_workspace_and_plan():
         assert 1 <= rb <= N // 16 and 1 <= c <= 8 and c == -(-(N // 16) // rb)
         assert ws == (ks * M * N * 4 if ks > 1 else 0)
         assert zq.gemm_w8a16_stream_plan(M, N, K, 0)[1] == 1
-    assert zq.gemm_w8a16_workspace_bytes(100, 2048, 8192) == zq.gemm_w8a16_workspace_bytes(64, 2048, 8192) > 0
-    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) == 0      # tiled above 128 tokens
+    # 65 to 128 tokens: at least what the 64-token streaming launches need, more where the tiled schedule
+    # with a K split is the faster choice
+    assert zq.gemm_w8a16_workspace_bytes(100, 2048, 8192) >= zq.gemm_w8a16_workspace_bytes(64, 2048, 8192) > 0
+    assert zq.gemm_w8a16_workspace_bytes(100, 18432, 6144) == zq.gemm_w8a16_workspace_bytes(64, 18432, 6144)
+    # above 128 tokens: the tiled schedule, which splits K where its tiles would leave most of the chip idle
+    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) % (129 * 2048 * 4) == 0
+    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) >= 2 * 129 * 2048 * 4
+    assert zq.gemm_w8a16_workspace_bytes(4096, 4096, 4096) == 0
     assert zq.gemm_w8a16_workspace_bytes(16, 2048, 1000) == 0       # K not a multiple of 256: untiled
     with pytest.raises(zq.ZQError):
         zq.gemm_w8a16_stream_plan(65, 2048, 8192)

@@ -10,7 +10,7 @@ from helpers import assert_bit_equal, assert_out_close, dev, freivalds_gpu, host
 
 pytestmark = pytest.mark.gpu
 
-SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK, TILE256X128, TILE256X192 = range(7)
+SIMPLE, TILE128, TILE256, SKINNY, SKINNY_SPLITK, TILE256X128, TILE256X192, TILE_SPLITK = range(8)
 
 
 @pytest.fixture(scope="module")
@@ -87,6 +87,10 @@ SHAPES = [
     # strips per row block, one to four strips per workgroup)
     (SKINNY, 1, 2048, 4096, 128), (SKINNY, 32, 1040, 4352, 65), (SKINNY, 17, 4112, 8192, 1), (SKINNY, 5, 80, 6400, 5),
     (SKINNY, 16, 12288, 4096, 96), (SKINNY, 9, 10000, 4864, 25),
+    # 128x128 tiles with K split over workgroups and the epilogue in a second kernel: ragged in M, N and K,
+    # two to eight splits, uneven stage counts per split, at most 128 tokens where K is no multiple of 256
+    (TILE_SPLITK, 130, 1024, 4096, 64), (TILE_SPLITK, 300, 400, 2048, 25), (TILE_SPLITK, 129, 272, 4000, 17),
+    (TILE_SPLITK, 200, 2064, 4096, 3), (TILE_SPLITK, 64, 528, 1920, 11), (TILE_SPLITK, 256, 1040, 3200, 65),
     # K split 3- to 12-fold, with ragged strip counts
     (SKINNY_SPLITK, 1, 2048, 8192, 128), (SKINNY_SPLITK, 8, 256, 4096, 16), (SKINNY_SPLITK, 32, 2048, 8192, 128),
     (SKINNY_SPLITK, 64, 1024, 6144, 64), (SKINNY_SPLITK, 13, 80, 2304, 5), (SKINNY_SPLITK, 33, 2064, 8192, 3),
@@ -106,7 +110,7 @@ def test_gemm_against_oracle(zq, orc, bits, variant, M, N, K, g):
     rng = zq_inputs.rng_for(4, variant * 1000 + M + N + K + bits)
     xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
     ws = None
-    if variant == SKINNY_SPLITK:
+    if variant in (SKINNY_SPLITK, TILE_SPLITK):
         nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
         if nbytes == 0:
             pytest.skip("shape does not split")

@@ -40,6 +40,8 @@ SHAPES = [
     (515, 1024, 400, 64), (300, 1040, 1008, 65),       # K not a multiple of the stage depth
     # ... and with a K split
     (32, 2048, 8192, 128), (7, 528, 24576, 11), (64, 4112, 16384, 1), (1, 2048, 8192, 128),
+    # above 128 tokens with few tiles and a long K: the tiled schedule splits K (fp32 partials, second kernel)
+    (130, 1024, 4096, 64), (300, 400, 2048, 25), (256, 2064, 2000, 3), (129, 272, 8192, 17),
     # 65 to 128 tokens: two streaming launches over row halves (second half ragged, one row, full), also with a K split
     (65, 1024, 1536, 64), (100, 6144, 2048, 128), (128, 2064, 512, 3), (90, 2048, 8192, 128), (128, 528, 24576, 11),
 ]
