@@ -108,8 +108,12 @@ zq_status zq_gelu_quant_tokenwise(const void *h_fp16, const void *bias_fp16, int
 
 /*
  * Bytes of scratch the GeMM calls can use for (M,N,K) with w_bits in {8,4}.
- * Small-M shapes split the reduction over workgroups and keep INT32 partial
- * sums there.  0 means no scratch is ever used for that shape.
+ * Shapes with few output rows or few output tiles against a long K split the
+ * reduction over workgroups and keep INT32 partial sums there (up to 128
+ * tokens in the weight-streaming schedule; above that, where 128x128 tiles
+ * would occupy less than half the chip, in the tiled schedule, whose epilogue
+ * then runs as a second kernel).  0 means no scratch is ever used for that
+ * shape.  The result never depends on the order in which workgroups finish.
  */
 size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
 
@@ -219,8 +223,9 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
  *             128 split K across workgroups where that is faster (fp32 partials; the result
  *             does not depend on the order in which workgroups finish)
  * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (up to 128 tokens the streaming
- * schedule needs K % 256 == 0, and 65 to 128 tokens run as two launches of it over row halves; other
- * small shapes run an untiled schedule).  The codes are converted to
+ * schedule needs K % 256 == 0, and 65 to 128 tokens run as two launches of it over row halves unless
+ * the tiled schedule with a K split is the faster choice for the shape and the workspace allows it;
+ * other small shapes run an untiled schedule).  The codes are converted to
  * FP16 exactly; the sum is accumulated in fp32 on the FP16 matrix cores, so unlike the INT8 calls
  * the result is reproducible but not bit-defined by the inputs alone (tolerance in the tests).
  * Calls that split K must not overlap with other GeMM calls on the same device.
@@ -231,8 +236,8 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
                                 size_t workspace_bytes, zq_stream stream);
 
 /*
- * Workspace that lets zq_gemm_w8a16_dequant split K for this shape (0: the call never splits, e.g.
- * above 128 tokens), and the cut its streaming schedule takes for up to 64 tokens (arguments and
+ * Workspace that lets zq_gemm_w8a16_dequant split K for this shape (0: the call never splits),
+ * and the cut its streaming schedule takes for up to 64 tokens (arguments and
  * results as zq_gemm_stream_plan; the cut is the INT8 call's unless that one divides strips into
  * K ranges, which this schedule does not do).  Host-only; launch nothing.
  */

@@ -33,6 +33,8 @@ CASES = [
     (TILE256, 300, 528, 512, 33), (TILE256X128, 300, 400, 512, 25), (6, 300, 400, 512, 25), (SKINNY, 8, 6144, 2048, 128),
     (SKINNY, 100, 768, 768, 48), (SKINNY_SPLITK, 33, 2064, 8192, 3), (-1, 128, 4096, 1024, 64),
     (-1, 16, 4096, 1024, 64),
+    # the tiled schedule with a K split: GeLU in the second kernel, then the row quantizer
+    (7, 300, 400, 2048, 25), (-1, 192, 1024, 4096, 64),
 ]
 
 
@@ -48,9 +50,12 @@ def test_gemm_gelu_quant_against_oracle(zq, orc, variant, M, N, K, g, bits, appr
     # scales that put the pre-activation where GeLU bends: |u| of a few units
     s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
     nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
-    if variant == SKINNY_SPLITK and nbytes == 0:
+    if variant in (SKINNY_SPLITK, 7) and nbytes == 0:
         pytest.skip("shape does not split")
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda") if variant in (SKINNY_SPLITK, -1) else None
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda") if variant in (SKINNY_SPLITK, 7, -1) else None
+    if (variant, M) == (-1, 192):
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nbytes)) == "tile128_splitk"
+        assert zq.gemm_quantizes_in_kernel(M, N, K, bits, nbytes) == 0
     prev = zq.force_gemm_variant(variant)
     try:
         g16, gq, s = zq.zq_gemm_gelu_quant_tokenwise(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias),
