@@ -26,6 +26,11 @@
 // through device memory and write INT8 codes from the accumulator registers
 // (see the state block below and the end of the kernel).
 //
+// KSPLIT = 1 serves shapes with so few tiles that most compute units would
+// idle while each tile walks a long K: several workgroups share a tile, each
+// over its own range of K stages, and write raw accumulators to a workspace;
+// splitk_finish_kernel adds them and applies the epilogue.
+//
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
 // in that XCD's L2.
