@@ -77,8 +77,8 @@ def test_stream_plan_covers_the_matrix():
             assert c == -(-strips // rb)                  # the fullest row block fits the workgroup
             if offered == 0:
                 assert ks == 1
-            else:
-                assert ks > 1 and ws == ks * M * N * 4 and strips <= 8192
+            elif ks > 1:                                  # (the workspace may also be another schedule's)
+                assert ws >= ks * M * N * 4 and strips <= 8192
     with pytest.raises(zq.ZQError):
         zq.gemm_stream_plan(129, 1024, 1024)
     with pytest.raises(zq.ZQError):
@@ -266,7 +266,11 @@ def test_tile_k_split_dispatch():
         assert zq.gemm_workspace_bytes(M, N, K, 4) == ws            # the INT4 call splits alike
     for (M, N, K) in [(1024, 4096, 4096), (384, 4096, 4096), (256, 4096, 1024), (4096, 4096, 1024), (129, 12288, 4096)]:
         assert zq.gemm_workspace_bytes(M, N, K, 8) == 0             # enough tiles, or K too short to pay
-    assert zq.gemm_variant_name(zq.gemm_choose_variant(100, 4096, 4096, 8, 1 << 30)) == "skinny"
+    # 65 to 128 tokens: the K split where K is long, streaming otherwise and always up to 64 tokens
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(100, 4096, 4096, 8, 1 << 30)) == "tile128_splitk"
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(100, 4096, 4096, 8, 0)) == "skinny"
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(100, 2048, 2048, 8, 1 << 30)) == "skinny"
+    assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 4096, 4096, 8, 1 << 30)) == "skinny"
 
 
 def test_w8a16_validation():
