@@ -232,7 +232,25 @@ FULL = [
 def test_full_size_workloads(zq, orc, name, M):
     print("full", name, M, flush=True)
     K, N, g, bits = zq_inputs.LINEARS[name]
-    rng = zq_inputs.rng_for(int(name[1]), M)
+    _large_shape_check(zq, orc, name, M, N, K, g, bits, zq_inputs.rng_for(int(name[1]), M))
+
+
+# Token counts between decode and prefill on the workload matrices: the schedules with a K split
+# (tiles above 64 tokens, streaming below) at sizes the oracle cannot cover element by element.
+MID = [("c4_out", 192), ("c4_ffc2", 128), ("c4_ffc2", 320), ("c3_ffc2", 1024), ("c5_ffc2", 100), ("c3_out", 512)]
+
+
+@pytest.mark.parametrize("name,M", MID)
+def test_mid_token_counts_on_workload_matrices(zq, orc, name, M):
+    K, N, g, bits = zq_inputs.LINEARS[name]
+    nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+    print("mid", name, M, zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nbytes)), flush=True)
+    _large_shape_check(zq, orc, name, M, N, K, g, bits, zq_inputs.rng_for(int(name[1]), 7000 + M))
+
+
+def _large_shape_check(zq, orc, name, M, N, K, g, bits, rng):
+    """Sampled rows against the oracle, the Freivalds identity on every accumulator, and the FP16
+    output against the epilogue of the accumulators everywhere."""
     g_t = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED + M)
     qmax = 127 if bits == 8 else 7
     xq_t = torch.randint(-127, 128, (M, K), generator=g_t, device="cuda", dtype=torch.int8)
