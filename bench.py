@@ -107,6 +107,8 @@ class FFCPair:
         self.o = torch.empty((tokens, hidden), dtype=torch.float16, device=d)
         self.acc1 = torch.empty((tokens, ffn), dtype=torch.int32, device=d)      # only the unfused ablation uses these
         self.acc2 = torch.empty((tokens, hidden), dtype=torch.int32, device=d)
+        # workspace of the fused call: its GeMM kernel exchanges row maxima through it
+        self.ws = zq.new_workspace(zq.gemm_quant_workspace_bytes(tokens, ffn, hidden, 8))
         self.ops = 2.0 * tokens * (hidden * ffn + ffn * hidden)
         self.gemm_ops = 2.0 * tokens * hidden * ffn          # per GeMM launch (both are equal)
 
@@ -132,11 +134,11 @@ class FFCPair:
         """GeMM 1 with bias + GeLU + token-wise quantization inside the GeMM kernel; the FP16 activation
         is never written (the second GeMM only reads the codes)."""
         self.zq.zq_gemm_gelu_quant_tokenwise(self.xq, self.st, self.wq1, self.sw1, self.b1,
-                                             out=(None, self.hq, self.st2), keep_g=False)
+                                             out=(None, self.hq, self.st2), keep_g=False, workspace=self.ws)
 
     def gemm1_gelu_keep(self, _=0):
         self.zq.zq_gemm_gelu_quant_tokenwise(self.xq, self.st, self.wq1, self.sw1, self.b1,
-                                             out=(self.h, self.hq, self.st2))
+                                             out=(self.h, self.hq, self.st2), workspace=self.ws)
 
     def fused_step(self, _=0):
         """Same layer with bias + GeLU in the epilogue of the first GeMM (three calls instead of four)."""
@@ -311,7 +313,7 @@ def time_gemm(zq, name, M, reps_target=40):
         sets.append((xq, st, wq, sw, out))
     bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
     nws = zq.gemm_workspace_bytes(M, N, K, bits)
-    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nws)
     fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
 
     def run(i):
@@ -370,7 +372,7 @@ def time_gemm_a16(zq, name, M, reps_target=40):
     bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
     out = torch.empty((M, N), dtype=torch.float16, device="cuda")
     nws = zq.gemm_w8a16_workspace_bytes(M, N, K)
-    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nws)
 
     def run(i):
         wq, sw = sets[i % nset]

@@ -17,17 +17,18 @@
  * Conventions shared by every call
  *   - Every pointer is a DEVICE pointer owned by the caller, valid on the
  *     current HIP device, 16-byte aligned, and sized as documented.  The
- *     library allocates nothing and frees nothing.  It owns two small pieces
- *     of device memory (file-scope arrays, one copy per device): arrival
- *     counters of the K-split GeMM schedules and the exchange slots of the
- *     GeMM calls that quantize their output inside the kernel.  Both are left
- *     ready for the next call by the kernels themselves; calls that use the
- *     same piece must not run at the same time on one device (see
- *     zq_gemm_i8_dequant and zq_gemm_gelu_quant_tokenwise).
+ *     library allocates nothing, frees nothing and keeps no device state of
+ *     its own: whatever the kernels of one call exchange among themselves
+ *     (arrival counters and partial sums of the K-split schedules, the row
+ *     maxima of the calls that quantize their output inside the GeMM kernel)
+ *     lives in the caller's workspace (see zq_workspace_init).  Calls on
+ *     different workspaces are independent and may run at the same time on
+ *     different streams.
  *   - Matrices are dense row-major.  "fp16" is IEEE binary16.
  *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream)
  *     and the call returns without synchronising.  Outputs must not alias
- *     inputs.  Calls sharing a workspace must be ordered on one stream.
+ *     inputs.  Calls sharing a workspace must be ordered on one stream (or by
+ *     events): two of them running at once corrupt each other.
  *   - Arguments are validated on the host before any HIP call; a failed check
  *     returns an error code and launches nothing.  A failed launch returns
  *     ZQ_ERR_HIP.
@@ -61,8 +62,27 @@ typedef enum {
 
 typedef void *zq_stream;
 
-/* Largest reduction length accepted: K * 127 * 127 must stay below 2^31. */
+/* Largest reduction length accepted: K * 127 * 127 must stay below 2^31.  With INT4 weights the
+ * kernels carry the nibbles as code * 16 and the code -8 is legal input, so K * 127 * 128 must. */
 #define ZQ_MAX_K 133143
+#define ZQ_MAX_K_W4 132104
+
+/*
+ * GeMM workspace.  A workspace is device memory the caller allocates once and hands to the GeMM
+ * calls.  Its first ZQ_WORKSPACE_FIXED_BYTES hold what the kernels of a call exchange (control
+ * words, 8192 arrival counters, 2^19 eight-byte slots for row maxima); partial sums of the
+ * K-split schedules follow.  zq_workspace_init zeroes the fixed part (one small kernel on
+ * `stream`, capturable) and must have completed, in stream order, before the first GeMM call
+ * that receives the workspace; afterwards only GeMM calls may write to it, and every call leaves
+ * the fixed part ready for the next one, whatever its shape or kind.  A workspace that was never
+ * initialised, or that something else wrote to, gives undefined results (never a fault).
+ * Sizes: zq_gemm_workspace_bytes / zq_gemm_quant_workspace_bytes / zq_gemm_w8a16_workspace_bytes;
+ * a buffer of the largest of them over the shapes of a model serves all its calls.
+ *   workspace        device, 16-byte aligned;  workspace_bytes >= ZQ_WORKSPACE_FIXED_BYTES
+ * Errors: ZQ_ERR_NULL, ZQ_ERR_SHAPE (too small), ZQ_ERR_ALIGN, ZQ_ERR_HIP.
+ */
+#define ZQ_WORKSPACE_FIXED_BYTES 4227328
+zq_status zq_workspace_init(void *workspace, size_t workspace_bytes, zq_stream stream);
 
 const char *zq_status_string(zq_status st);
 
@@ -107,15 +127,22 @@ zq_status zq_gelu_quant_tokenwise(const void *h_fp16, const void *bias_fp16, int
                                   void *y_out, int y_dtype, zq_stream stream);
 
 /*
- * Bytes of scratch the GeMM calls can use for (M,N,K) with w_bits in {8,4}.
+ * Bytes of workspace the GeMM calls can use for (M,N,K) with w_bits in {8,4}.
  * Shapes with few output rows or few output tiles against a long K split the
  * reduction over workgroups and keep INT32 partial sums there (up to 128
  * tokens in the weight-streaming schedule; above that, where 128x128 tiles
  * would occupy less than half the chip, in the tiled schedule, whose epilogue
- * then runs as a second kernel).  0 means no scratch is ever used for that
- * shape.  The result never depends on the order in which workgroups finish.
+ * then runs as a second kernel).  The figure is ZQ_WORKSPACE_FIXED_BYTES plus
+ * the partial sums, or 0 when no schedule for that shape splits K.  The result
+ * of a call never depends on the order in which workgroups finish.
+ *
+ * zq_gemm_quant_workspace_bytes: the same for a call that also asks for the
+ * token-wise quantization of its output (out_q / gq_out): at least
+ * ZQ_WORKSPACE_FIXED_BYTES where the GeMM kernel itself would quantize (see
+ * zq_gemm_gelu_quant_tokenwise), so never less than zq_gemm_workspace_bytes.
  */
 size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
+size_t zq_gemm_quant_workspace_bytes(int M, int N, int K, int w_bits);
 
 /*
  * INT8 GeMM with the dequantization epilogue (Sec. 4.3; App. D).
@@ -123,16 +150,15 @@ size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits);
  *   out[m,n] = fp16( float(acc) * s_tok[m] * s_w[n / (N/groups)] + bias[n] )
  *   xq int8 [M,K]; s_tok fp32 [M]; wq int8 [N,K]; s_w fp32 [groups];
  *   bias_fp16 [N] or NULL; out_fp16 [M,N].
- *   Requires N % groups == 0, (N/groups) % 16 == 0, K % 16 == 0, K <= ZQ_MAX_K,
+ *   Requires N % groups == 0, (N/groups) % 16 == 0, K % 16 == 0, K <= ZQ_MAX_K (ZQ_MAX_K_W4 with INT4 weights),
  *   and each operand (xq, wq) below 2 GiB (32-bit buffer offsets in the kernels).
  *   acc_out   NULL, or int32 [M,N] receiving the accumulator (parity tap).
  *   out_q / out_s_tok  both NULL, or int8 [M,N] / fp32 [M]: the token-wise
  *             quantization of the FP16-rounded `out`, ready for the next GeMM.
- *   workspace NULL, or device scratch of workspace_bytes.  With less than
- *             zq_gemm_workspace_bytes(...) the call still succeeds, on a
- *             kernel that needs none.  Calls that use it (K split) share the
- *             library's arrival counters and must not overlap with each other
- *             on one device.
+ *   workspace NULL, or an initialised workspace (zq_workspace_init) of
+ *             workspace_bytes.  With less than zq_gemm_workspace_bytes(...)
+ *             (zq_gemm_quant_workspace_bytes with out_q) the call still
+ *             succeeds, on kernels that need none.
  */
 zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w,
                              int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
@@ -151,10 +177,10 @@ zq_status zq_gemm_w4a8_dequant(const int8_t *xq, const float *s_tok, const uint8
                                void *workspace, size_t workspace_bytes, zq_stream stream);
 
 /*
- * The two operators of the unfused pipeline (Fig. 2, left; Sec. 4.3 calls the
- * stand-alone quantizer "an efficient parallel implementation of the
- * quantization operator"), kept as calls of their own: for layers whose
- * producer is not LayerNorm or GeLU, and to measure what the fusions save.
+ * The two operators of the unfused pipeline (Fig. 2, left; App. D describes
+ * the stand-alone quantization operator that the fused kernels replace), kept
+ * as calls of their own: for layers whose producer is not LayerNorm or GeLU,
+ * and to measure what the fusions save.
  *
  * zq_quantize_tokenwise: token-wise INT8 quantization (App. A.2, one scale per
  * row) of an FP16 tensor.
@@ -195,16 +221,21 @@ zq_status zq_dequantize_acc(const int32_t *acc, const float *s_tok, const float 
  * N <= 32768 (a row of g is quantized from registers).  Errors as the GeMM calls.
  *
  * Where the quantization happens.  On the tiled schedules (large token counts)
- * the GeMM kernel itself quantizes: the tiles that share a band of token rows
- * exchange their row maxima through device memory owned by the library, wait
- * for each other, and write the codes from their accumulator registers, so g
- * is not read back (and not written at all when g_fp16 is NULL).  The same
- * holds for out_q / out_s_tok of zq_gemm_i8_dequant and zq_gemm_w4a8_dequant.
- * Elsewhere a second kernel quantizes the FP16 rows just written.  Both ways
- * give the same bits.  Calls that quantize in the kernel must not overlap on
- * one device (they share the exchange memory).  It needs N <= 16384 and
- * (M rounded up to 256) * ceil(N / 256) <= 2^20; beyond that the second
- * kernel is used.
+ * the GeMM kernel itself quantizes when the call has a workspace: the tiles
+ * that share a band of token rows exchange their row maxima through the
+ * workspace, wait for each other, and write the codes from their accumulator
+ * registers, so g is not read back (and not written at all when g_fp16 is
+ * NULL).  The same holds for out_q / out_s_tok of zq_gemm_i8_dequant and
+ * zq_gemm_w4a8_dequant.  Elsewhere, and without a workspace, a second kernel
+ * quantizes the FP16 rows just written.  Both ways give the same bits.  It
+ * needs a band of tiles to fit a quarter of the device's compute units (N <=
+ * 16384 on 256 of them) and (M rounded up to the tile edge) * (tiles along N)
+ * <= 2^19 exchange slots; beyond that the second kernel is used.
+ * The wait of a tile for its band is bounded (about a second).  It cannot run
+ * out while workgroups are started in id order, which is how the hardware
+ * dispatches them; if it does all the same, the rows concerned come back with
+ * out_s_tok = NaN and codes -128 (a value the quantizer never produces) in the
+ * columns of the tiles that gave up, and zq_quant_wait_expired counts it.
  */
 zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, const void *wq, int w_bits,
                                        const float *s_w, int groups, const void *bias_fp16, int approx_tanh, int M,
@@ -219,16 +250,15 @@ zq_status zq_gemm_gelu_quant_tokenwise(const int8_t *xq, const float *s_tok, con
  *   x_fp16    in,  fp16 [M,K] row-major                      (device)
  *   wq        in,  int8 [N,K];  s_w  fp32 [groups];  bias_fp16  fp16 [N] or NULL   (device)
  *   out_fp16  out, fp16 [M,N]                                (device)
- *   workspace scratch of zq_gemm_w8a16_workspace_bytes(M, N, K) bytes or NULL: lets token counts up to
- *             128 split K across workgroups where that is faster (fp32 partials; the result
- *             does not depend on the order in which workgroups finish)
+ *   workspace an initialised workspace (zq_workspace_init) of zq_gemm_w8a16_workspace_bytes(M, N, K)
+ *             bytes, or NULL: lets small token counts split K across workgroups where that is
+ *             faster (fp32 partials; the result does not depend on the order in which workgroups finish)
  * K % 16 == 0, K <= ZQ_MAX_K, N % groups == 0, (N/groups) % 16 == 0 (up to 128 tokens the streaming
  * schedule needs K % 256 == 0, and 65 to 128 tokens run as two launches of it over row halves unless
  * the tiled schedule with a K split is the faster choice for the shape and the workspace allows it;
  * other small shapes run an untiled schedule).  The codes are converted to
  * FP16 exactly; the sum is accumulated in fp32 on the FP16 matrix cores, so unlike the INT8 calls
  * the result is reproducible but not bit-defined by the inputs alone (tolerance in the tests).
- * Calls that split K must not overlap with other GeMM calls on the same device.
  * Errors: ZQ_ERR_NULL, ZQ_ERR_SHAPE, ZQ_ERR_ALIGN, ZQ_ERR_HIP.
  */
 zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const float *s_w, int groups,
@@ -261,14 +291,16 @@ int zq_debug_force_gemm_variant(int variant);
  * zq_debug_set_in_kernel_quant: test and ablation hook; on = 0 makes every
  * call use the second kernel.  Process-wide; returns the previous value.
  *
- * zq_quant_wait_expired: the wait of a tile for the rest of its band is
- * bounded (about a second); *count_out receives the number of threads whose wait
- * ran out since the last call of this function, 0 in every correct run (their
- * rows would be wrong).  Synchronises the device.  ZQ_ERR_NULL, ZQ_ERR_HIP.
+ * zq_quant_wait_expired: *count_out receives the number of threads (one per
+ * tile and token row) whose bounded wait ran out in calls on this workspace
+ * since the last call of this function, 0 in every correct run, and the
+ * count is reset.  Synchronous: it copies one word from the device, so every
+ * call on the workspace must have been waited for.  ZQ_ERR_NULL, ZQ_ERR_ALIGN,
+ * ZQ_ERR_HIP.
  */
 int zq_gemm_quantizes_in_kernel(int M, int N, int K, int w_bits, size_t workspace_bytes);
 int zq_debug_set_in_kernel_quant(int on);
-zq_status zq_quant_wait_expired(int *count_out);
+zq_status zq_quant_wait_expired(void *workspace, int *count_out);
 
 /* Name of schedule `variant` (NULL when out of range), and the schedule the
  * dispatcher would choose for a shape. */

@@ -16,6 +16,10 @@ from .binding import (  # noqa: F401
     gemm_w8a16_workspace_bytes,
     gemm_variant_name,
     gemm_workspace_bytes,
+    gemm_quant_workspace_bytes,
+    new_workspace,
+    zq_workspace_init,
+    WORKSPACE_FIXED_BYTES,
     force_gemm_variant,
     lib,
     tune_clear,

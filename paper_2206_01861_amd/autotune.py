@@ -103,7 +103,7 @@ def tune_shape(M, N, K, bits, m_lo=None, m_hi=None, verbose=False):
         except zq.ZQError:
             continue
         nws = zq.gemm_workspace_bytes(M, N, K, bits)
-        wsb = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+        wsb = zq.new_workspace(nws)
         if zq.gemm_choose_variant(M, N, K, bits, nws) != v:
             continue                                  # not runnable for this shape
         us = _time_us(lambda i: fn(xq, st, ws_[i], sw, bias, workspace=wsb, out=out), nsets)

@@ -20,6 +20,7 @@ SYMBOLS = [
     "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant", "zq_gemm_w8a16_workspace_bytes",
     "zq_gemm_w8a16_stream_plan",
     "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
+    "zq_workspace_init", "zq_gemm_quant_workspace_bytes",
 ]
 
 
@@ -79,7 +80,11 @@ def lib():
     L.zq_debug_set_in_kernel_quant.restype = ci
     L.zq_debug_set_in_kernel_quant.argtypes = [ci]
     L.zq_quant_wait_expired.restype = ci
-    L.zq_quant_wait_expired.argtypes = [ctypes.POINTER(ci)]
+    L.zq_quant_wait_expired.argtypes = [vp, ctypes.POINTER(ci)]
+    L.zq_workspace_init.restype = ci
+    L.zq_workspace_init.argtypes = [vp, sz, vp]
+    L.zq_gemm_quant_workspace_bytes.restype = sz
+    L.zq_gemm_quant_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.zq_debug_force_gemm_variant.restype = ci
     L.zq_debug_force_gemm_variant.argtypes = [ci]
     L.zq_gemm_variant_name.restype = ctypes.c_char_p
@@ -125,6 +130,27 @@ def gemm_workspace_bytes(M, N, K, w_bits=8):
     return int(lib().zq_gemm_workspace_bytes(M, N, K, w_bits))
 
 
+def gemm_quant_workspace_bytes(M, N, K, w_bits=8):
+    """Workspace a GeMM call that also quantizes its output can use (zq_gemm_quant_workspace_bytes)."""
+    return int(lib().zq_gemm_quant_workspace_bytes(M, N, K, w_bits))
+
+
+WORKSPACE_FIXED_BYTES = 4227328      # ZQ_WORKSPACE_FIXED_BYTES of include/zq.h
+
+
+def zq_workspace_init(workspace):
+    """Zero the fixed part of a workspace (uint8 CUDA tensor) on torch's current stream."""
+    _dev(workspace, torch.uint8, "workspace")
+    _check(lib().zq_workspace_init(_ptr(workspace), workspace.numel(), _stream()))
+    return workspace
+
+
+def new_workspace(nbytes, device="cuda"):
+    """Allocate (torch) and initialise a workspace of at least nbytes; the smallest legal one if nbytes is less."""
+    ws = torch.empty(max(int(nbytes), WORKSPACE_FIXED_BYTES), dtype=torch.uint8, device=device)
+    return zq_workspace_init(ws)
+
+
 def force_gemm_variant(variant):
     """Force a GeMM schedule (-1 = automatic).  Returns the previous setting."""
     return lib().zq_debug_force_gemm_variant(int(variant))
@@ -149,10 +175,11 @@ def set_in_kernel_quant(on):
     return bool(lib().zq_debug_set_in_kernel_quant(1 if on else 0))
 
 
-def quant_wait_expired():
-    """Workgroups whose bounded wait ran out since the last call (0 in a correct run); synchronises."""
+def quant_wait_expired(workspace):
+    """Threads whose bounded wait ran out in calls on this workspace since the last query (0 in a
+    correct run).  The caller synchronises first."""
     c = ctypes.c_int(0)
-    _check(lib().zq_quant_wait_expired(ctypes.byref(c)))
+    _check(lib().zq_quant_wait_expired(_ptr(workspace), ctypes.byref(c)))
     return c.value
 
 
@@ -249,6 +276,28 @@ def zq_gelu_quant_tokenwise(h_fp16, bias_fp16=None, approx_tanh=False, y_dtype=N
     return xq, s_tok, y
 
 
+def _out_shape(t, M, N, name):
+    if tuple(t.shape) != (M, N):
+        raise ValueError("%s must be [%d, %d], got %s" % (name, M, N, tuple(t.shape)))
+
+
+def _gemm_shapes(M, N, K, wq, w_bits, s_tok, bias_fp16):
+    """The C ABI trusts the sizes it is given: check every tensor against (M, N, K) before the call."""
+    if wq.dim() != 2 or wq.shape[1] * (8 // w_bits) != K:
+        raise ValueError("wq must be [N, %s] for K = %d, got %s" % ("K" if w_bits == 8 else "K/2", K, tuple(wq.shape)))
+    if s_tok is not None and s_tok.numel() != M:
+        raise ValueError("s_tok must hold %d scales, got %d" % (M, s_tok.numel()))
+    if bias_fp16 is not None and bias_fp16.numel() != N:
+        raise ValueError("bias must hold %d values, got %d" % (N, bias_fp16.numel()))
+
+
+def _ws_bytes(workspace):
+    if workspace is None:
+        return 0
+    _dev(workspace, torch.uint8, "workspace")
+    return workspace.numel()
+
+
 def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspace, out, acc_out=None):
     _dev(xq, torch.int8, "xq")
     _dev(s_tok, torch.float32, "s_tok")
@@ -258,15 +307,17 @@ def _gemm(fn, wdtype, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant, workspac
         _dev(bias_fp16, torch.float16, "bias_fp16")
     M, K = xq.shape
     N = wq.shape[0]
+    _gemm_shapes(M, N, K, wq, 8 if wdtype == torch.int8 else 4, s_tok, bias_fp16)
     dev = xq.device
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=dev)
+    _out_shape(_dev(out, torch.float16, "out"), M, N, "out")
     acc = acc_out if acc_out is not None else (torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None)
     if acc is not None:
-        _dev(acc, torch.int32, "acc_out")
+        _out_shape(_dev(acc, torch.int32, "acc_out"), M, N, "acc_out")
     out_q = torch.empty((M, N), dtype=torch.int8, device=dev) if requant else None
     out_s = torch.empty(M, dtype=torch.float32, device=dev) if requant else None
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _ws_bytes(workspace)
     _check(fn(_ptr(xq), _ptr(s_tok), _ptr(wq), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N, K, _ptr(out),
               _ptr(acc), _ptr(out_q), _ptr(out_s), _ptr(workspace), ws_bytes, _stream()))
     return out, acc, out_q, out_s
@@ -282,8 +333,6 @@ def zq_gemm_i8_dequant(xq, s_tok, wq, s_w, bias_fp16=None, want_acc=False, requa
 def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,
                          out=None, acc_out=None):
     """INT4-packed weights uint8 [N,K/2]; otherwise as zq_gemm_i8_dequant."""
-    if wq4.shape[1] * 2 != xq.shape[1]:
-        raise ValueError("wq4 must be [N, K/2]")
     return _gemm(lib().zq_gemm_w4a8_dequant, torch.uint8, xq, s_tok, wq4, s_w, bias_fp16, want_acc, requant,
                  workspace, out, acc_out)
 
@@ -312,6 +361,7 @@ def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh
         _dev(bias_fp16, torch.float16, "bias_fp16")
     M, K = xq.shape
     N = wq.shape[0]
+    _gemm_shapes(M, N, K, wq, w_bits, s_tok, bias_fp16)
     dev = xq.device
     g, gq, s = out if out is not None else (
         torch.empty((M, N), dtype=torch.float16, device=dev) if keep_g else None,
@@ -319,7 +369,12 @@ def zq_gemm_gelu_quant_tokenwise(xq, s_tok, wq, s_w, bias_fp16=None, approx_tanh
         torch.empty(M, dtype=torch.float32, device=dev))
     if not keep_g:
         g = None
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if g is not None:
+        _out_shape(_dev(g, torch.float16, "g"), M, N, "g")
+    _out_shape(_dev(gq, torch.int8, "gq"), M, N, "gq")
+    if _dev(s, torch.float32, "s_tok_out").numel() != M:
+        raise ValueError("s_tok_out must hold %d scales" % M)
+    ws_bytes = _ws_bytes(workspace)
     _check(lib().zq_gemm_gelu_quant_tokenwise(_ptr(xq), _ptr(s_tok), _ptr(wq), w_bits, _ptr(s_w), int(s_w.numel()),
                                               _ptr(bias_fp16), 1 if approx_tanh else 0, M, N, K, _ptr(g), _ptr(gq),
                                               _ptr(s), _ptr(workspace), ws_bytes, _stream()))
@@ -361,9 +416,11 @@ def zq_gemm_w8a16_dequant(x_fp16, wq, s_w, bias_fp16=None, workspace=None, out=N
         _dev(bias_fp16, torch.float16, "bias_fp16")
     M, K = x_fp16.shape
     N = wq.shape[0]
+    _gemm_shapes(M, N, K, wq, 8, None, bias_fp16)
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=x_fp16.device)
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _out_shape(_dev(out, torch.float16, "out"), M, N, "out")
+    ws_bytes = _ws_bytes(workspace)
     _check(lib().zq_gemm_w8a16_dequant(_ptr(x_fp16), _ptr(wq), _ptr(s_w), int(s_w.numel()), _ptr(bias_fp16), M, N, K,
                                        _ptr(out), _ptr(workspace), ws_bytes, _stream()))
     return out

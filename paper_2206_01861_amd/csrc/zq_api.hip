@@ -19,6 +19,7 @@ inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 
 constexpr int kMaxRow = 32768;   // longest row the fused front-ends keep in registers
 constexpr uint64_t kMaxOperandBytes = 1ull << 31;   // a GeMM operand must stay below 2 GiB
+static_assert(ZQ_WORKSPACE_FIXED_BYTES == zq::kWsFixedBytes, "the header states the size of the fixed part");
 
 zq_status check_rowquant(const void *in, const void *p0, const void *p1, int M, int K, const int8_t *xq,
                          const float *s_tok, const void *y_out, int y_dtype) {
@@ -40,7 +41,7 @@ zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, cons
     if ((out_q == nullptr) != (out_s_tok == nullptr)) return ZQ_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || groups <= 0) return ZQ_ERR_SHAPE;
     if ((N % groups) != 0 || ((N / groups) % 16) != 0) return ZQ_ERR_SHAPE;
-    if ((K % (w_bits == 4 ? 32 : 16)) != 0 || K > ZQ_MAX_K) return ZQ_ERR_SHAPE;
+    if ((K % (w_bits == 4 ? 32 : 16)) != 0 || K > (w_bits == 4 ? ZQ_MAX_K_W4 : ZQ_MAX_K)) return ZQ_ERR_SHAPE;
     // the kernels address both operands through 32-bit buffer offsets
     if ((uint64_t)M * K >= kMaxOperandBytes || (uint64_t)N * K * w_bits / 8 >= kMaxOperandBytes) return ZQ_ERR_SHAPE;
     if (out_q != nullptr && N > kMaxRow) return ZQ_ERR_SHAPE;
@@ -58,7 +59,7 @@ zq_status gemm_common(const int8_t *xq, const float *s_tok, const void *wq, cons
     }
     // On the tiled schedules the output rows are quantized inside the GeMM kernel.
     const bool in_kernel = out_q != nullptr && g_in_kernel_quant.load() != 0 && is_tile_variant(variant) &&
-                           zq::gemm_tile_quant_supported(M, N);
+                           zq::gemm_tile_quant_supported(M, N, workspace_bytes);
     if (out == nullptr && !in_kernel) return ZQ_ERR_UNSUPPORTED;
     zq::GemmArgs a;
     a.xq = xq; a.s_tok = s_tok; a.wq = wq; a.s_w = s_w; a.groups = groups; a.bias = bias;
@@ -161,6 +162,24 @@ size_t zq_gemm_workspace_bytes(int M, int N, int K, int w_bits) {
         if (need > best && zq::gemm_variant_supports(v, M, N, K, w_bits, need)) best = need;
     }
     return best;
+}
+
+size_t zq_gemm_quant_workspace_bytes(int M, int N, int K, int w_bits) {
+    if (M <= 0 || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return 0;
+    size_t need = zq_gemm_workspace_bytes(M, N, K, w_bits);
+    // the schedule of a caller who offers exactly `need` (a larger offer changes nothing)
+    const int variant = zq_gemm_choose_variant(M, N, K, w_bits, need);
+    if (is_tile_variant(variant) && zq::gemm_tile_quant_supported(M, N, zq::kWsFixedBytes) && need < zq::kWsFixedBytes)
+        need = zq::kWsFixedBytes;
+    return need;
+}
+
+zq_status zq_workspace_init(void *workspace, size_t workspace_bytes, zq_stream stream) {
+    if (workspace == nullptr) return ZQ_ERR_NULL;
+    if (workspace_bytes < zq::kWsFixedBytes) return ZQ_ERR_SHAPE;
+    if (misaligned(workspace)) return ZQ_ERR_ALIGN;
+    return zq::launch_workspace_init(workspace, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? ZQ_OK
+                                                                                                      : ZQ_ERR_HIP;
 }
 
 zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w, int groups,
@@ -275,13 +294,19 @@ int zq_gemm_quantizes_in_kernel(int M, int N, int K, int w_bits, size_t workspac
     if (M <= 0 || N <= 0 || K <= 0 || (w_bits != 8 && w_bits != 4)) return 0;
     int variant = g_forced_variant.load();
     if (variant < 0) variant = zq_gemm_choose_variant(M, N, K, w_bits, workspace_bytes);
-    return (g_in_kernel_quant.load() != 0 && is_tile_variant(variant) && zq::gemm_tile_quant_supported(M, N)) ? 1 : 0;
+    return (g_in_kernel_quant.load() != 0 && is_tile_variant(variant) &&
+            zq::gemm_tile_quant_supported(M, N, workspace_bytes))
+               ? 1
+               : 0;
 }
 
-zq_status zq_quant_wait_expired(int *count_out) {
-    if (count_out == nullptr) return ZQ_ERR_NULL;
-    unsigned c = 0;
-    if (zq::quant_wait_expired(&c) != hipSuccess) return ZQ_ERR_HIP;
+zq_status zq_quant_wait_expired(void *workspace, int *count_out) {
+    if (workspace == nullptr || count_out == nullptr) return ZQ_ERR_NULL;
+    if (misaligned(workspace)) return ZQ_ERR_ALIGN;
+    unsigned *word = zq::ws_control(workspace) + 2;
+    unsigned c = 0, zero = 0;
+    if (hipMemcpy(&c, word, sizeof(unsigned), hipMemcpyDeviceToHost) != hipSuccess) return ZQ_ERR_HIP;
+    if (hipMemcpy(word, &zero, sizeof(unsigned), hipMemcpyHostToDevice) != hipSuccess) return ZQ_ERR_HIP;
     *count_out = (int)c;
     return ZQ_OK;
 }

@@ -114,11 +114,9 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
     // compute units when the caller's workspace holds the partial products.
     if (gemm_variant_supports(kGemmTileSplitK, M, N, K, w_bits, workspace_bytes)) return kGemmTileSplitK;
     // Tiled schedules.  The tiles of a launch all take the same time and a compute unit holds one of
-    // them (two of the four-wave 128x128 ones), so a launch lasts (rounds of tiles) x (time of a
-    // tile), and the time of a tile goes with its area times a factor for the operand bytes it moves
-    // per product.  Factors fitted to one-round measurements at K = 2048..6144 (256x256 = 1): 256x192
-    // 1.15, 128x128 on eight waves 1.85, two co-resident four-wave 128x128 tiles 4.1 each.  The
-    // 128x128 launcher itself takes eight waves up to 384 tiles and four beyond.
+    // them, so a launch lasts (rounds of tiles) x (time of a tile), and the time of a tile goes with
+    // its area times a factor for the operand bytes it moves per product.  Factors fitted to one-round
+    // measurements at K = 2048..6144 (256x256 = 1): 256x192 1.15, 128x128 1.85.
     constexpr long kComputeUnits = 256;
     const long rows256 = (M + 255) / 256;
     const long t256 = rows256 * ((N + 255) / 256);
@@ -127,8 +125,7 @@ extern "C" int zq_gemm_choose_variant(int M, int N, int K, int w_bits, size_t wo
     auto rounds = [](long tiles, long slots) { return (tiles + slots - 1) / slots; };
     const long c256 = rounds(t256, kComputeUnits) * 65536 * 100;
     const long c192 = rounds(t192, kComputeUnits) * 49152 * 115;
-    const long c128 = (t128 <= 384) ? rounds(t128, kComputeUnits) * 16384 * 185
-                                    : rounds(t128, 2 * kComputeUnits) * 16384 * 410;
+    const long c128 = rounds(t128, kComputeUnits) * 16384 * 185;
     if (c128 <= c256 && c128 <= c192) return kGemmTile128;
     return (c192 < c256) ? kGemmTile256x192 : kGemmTile256;
 }

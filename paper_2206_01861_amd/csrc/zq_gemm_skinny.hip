@@ -47,7 +47,6 @@ namespace zq {
 namespace {
 
 constexpr uint32_t kRsrcFlags = 0x00020000u;   // raw 32-bit buffer, gfx9 encoding
-constexpr int kMaxSharedStrips = 8192;         // arrival counters, one per 16-row strip that is split along K
 constexpr int kStageK = 256;                   // values of K per stage
 [[maybe_unused]] constexpr int kAuxDeviceCoherent = 0x10;        // sc1: coherent across the XCDs of the device
 constexpr int kMaxConsumers = 8;               // consumer waves per workgroup
@@ -145,11 +144,9 @@ __device__ __forceinline__ void stream_wait(int32x4 (&w)[LW]) {
 
 }  // namespace
 
-// Arrival counters of the strips that are split along K.  Zero when the library is loaded and
-// zero again after every call (the wave that completes a strip resets its counter), so no launch
-// is spent clearing them.  Shared by all calls on a device: GeMM calls that split K must not
-// overlap on one device.
-__device__ unsigned int g_strip_arrivals[kMaxSharedStrips];
+// The arrival counters of the strips that are split along K live in the caller's workspace (one per
+// strip, kMaxSharedStrips of them): zero after zq_workspace_init() and zero again after every call
+// (the wave that completes a strip resets its counter), so no launch is spent clearing them.
 
 struct StreamPlan {
     int strips;       // 16-row strips of the weight matrix (N / 16)
@@ -168,8 +165,8 @@ template <int MT, int WBITS, int DW, int R, int QSH = 0>
 __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
-    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int32_t *__restrict__ partial, StreamPlan plan,
-    int act) {
+    half_t *__restrict__ out, int32_t *__restrict__ acc_out, int32_t *__restrict__ partial,
+    unsigned *__restrict__ arrivals, StreamPlan plan, int act) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int LW = (WBITS == 8) ? 4 : 2;          // 16-byte weight loads per lane per stage
@@ -415,11 +412,11 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_kernel(
         wait_vmcnt<0>();                              // this wave's partial stores are acknowledged
         unsigned prev = 0;
         if (lane == 0)
-            prev = __hip_atomic_fetch_add(&g_strip_arrivals[strip], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            prev = __hip_atomic_fetch_add(arrivals + strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         prev = __builtin_amdgcn_readfirstlane(prev);
         if (prev != (unsigned)nseg - 1u) return;
         if (lane == 0)                                // leave the counter at zero for the next call
-            __hip_atomic_store(&g_strip_arrivals[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(arrivals + strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int o0 = 0; o0 < nseg; o0 += 4) {        // four partials per round trip
 #pragma unroll
             for (int oo = 0; oo < 4; ++oo) {
@@ -482,7 +479,7 @@ template <int MT, int DW, int R>
 __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kernel(
     const half_t *__restrict__ x, const uint8_t *__restrict__ wq, const float *__restrict__ s_w, int gs,
     const half_t *__restrict__ bias, int M, int N, int K, half_t *__restrict__ out, float *__restrict__ partial,
-    StreamPlan plan) {
+    unsigned *__restrict__ arrivals, StreamPlan plan) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int LW = 4;                             // 16-byte weight loads per lane per stage
@@ -645,11 +642,11 @@ __global__ __launch_bounds__(64 * (kMaxConsumers + 1)) void gemm_stream_a16_kern
         wait_vmcnt<0>();
         unsigned prev = 0;
         if (lane == 0)
-            prev = __hip_atomic_fetch_add(&g_strip_arrivals[strip], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            prev = __hip_atomic_fetch_add(arrivals + strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         prev = __builtin_amdgcn_readfirstlane(prev);
         if (prev != (unsigned)nseg - 1u) return;
         if (lane == 0)
-            __hip_atomic_store(&g_strip_arrivals[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(arrivals + strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt] = float32x4{0.0f, 0.0f, 0.0f, 0.0f};
         for (int o0 = 0; o0 < nseg; o0 += 4) {        // every partial, this wave's included, in split order
@@ -792,11 +789,16 @@ hipError_t launch_stream_q(const GemmArgs &a, const StreamPlan &plan, hipStream_
     const void *kernel = reinterpret_cast<const void *>(&gemm_stream_kernel<MT, WBITS, DW, R, QSH>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     if ((plan.consumers << QSH) > kMaxConsumers) return hipErrorInvalidValue;
+    const bool split = plan.k_splits > 1;
+    if (split && (a.workspace == nullptr ||
+                  a.workspace_bytes < kWsFixedBytes + (size_t)plan.k_splits * a.M * a.N * sizeof(int32_t)))
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL((gemm_stream_kernel<MT, WBITS, DW, R, QSH>), dim3(plan.row_blocks, plan.k_splits),
                        dim3(64 * ((plan.consumers << QSH) + 1)), lds, st, a.xq, a.s_tok,
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
-                       a.acc_out, reinterpret_cast<int32_t *>(a.workspace), plan, a.act);
+                       a.acc_out, split ? reinterpret_cast<int32_t *>(ws_partials(a.workspace)) : nullptr,
+                       split ? ws_counters(a.workspace) : nullptr, plan, a.act);
     return hipGetLastError();
 }
 template <int MT, int WBITS>
@@ -810,13 +812,13 @@ hipError_t launch_stream_t(const GemmArgs &a, const StreamPlan &plan, hipStream_
 
 }  // namespace
 
-// Workspace of the K-split schedule: one INT32 partial of M x N per split.  0 when the chosen cut
-// has no K split.
+// Workspace of the K-split schedule: the fixed part plus one INT32 partial of M x N per split.
+// 0 when the chosen cut has no K split.
 size_t stream_workspace_bytes(int M, int N, int K, int w_bits) {
     if (K / kStageK < 1) return 0;
     const StreamPlan plan = plan_stream(M, N, K, w_bits, true);
     if (plan.k_splits <= 1) return 0;
-    return (size_t)plan.k_splits * M * N * sizeof(int32_t);
+    return kWsFixedBytes + (size_t)plan.k_splits * M * N * sizeof(int32_t);
 }
 
 void stream_plan(int M, int N, int K, int w_bits, bool allow_split, int *row_blocks, int *k_splits, int *consumers,
@@ -836,11 +838,16 @@ hipError_t launch_stream_a16_t(const A16Args &a, const StreamPlan &plan, hipStre
     static std::atomic<uint64_t> configured{0};
     const void *kernel = reinterpret_cast<const void *>(&gemm_stream_a16_kernel<MT, DW, R>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
+    const bool split = plan.k_splits > 1;
+    if (split && (a.workspace == nullptr ||
+                  a.workspace_bytes < kWsFixedBytes + (size_t)plan.k_splits * a.M * a.N * sizeof(float)))
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL((gemm_stream_a16_kernel<MT, DW, R>), dim3(plan.row_blocks, plan.k_splits),
                        dim3(64 * (plan.consumers + 1)), lds, st, reinterpret_cast<const half_t *>(a.x),
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
-                       reinterpret_cast<float *>(a.workspace), plan);
+                       split ? reinterpret_cast<float *>(ws_partials(a.workspace)) : nullptr,
+                       split ? ws_counters(a.workspace) : nullptr, plan);
     return hipGetLastError();
 }
 }  // namespace
@@ -855,12 +862,13 @@ StreamPlan plan_stream_a16(int M, int N, int K, bool allow_split) {
 }
 }  // namespace
 
-// Workspace of the K-split schedule for FP16 activations: one fp32 partial of M x N per split.
+// Workspace of the K-split schedule for FP16 activations: the fixed part plus one fp32 partial of
+// M x N per split.
 size_t stream_a16_workspace_bytes(int M, int N, int K) {
     if (K / kStageK < 1) return 0;
     const StreamPlan plan = plan_stream_a16(M, N, K, true);
     if (plan.k_splits <= 1) return 0;
-    return (size_t)plan.k_splits * M * N * sizeof(float);
+    return kWsFixedBytes + (size_t)plan.k_splits * M * N * sizeof(float);
 }
 
 void stream_a16_plan(int M, int N, int K, bool allow_split, int *row_blocks, int *k_splits, int *consumers) {
@@ -874,7 +882,7 @@ hipError_t launch_gemm_a16_stream(const A16Args &a, bool allow_split, hipStream_
     StreamPlan plan = plan_stream_a16(a.M, a.N, a.K, allow_split);
     // never split further than the workspace holds (a schedule-table entry may ask for more splits
     // than the size the caller was told)
-    if (plan.k_splits > 1 && (size_t)plan.k_splits * a.M * a.N * sizeof(float) > a.workspace_bytes)
+    if (plan.k_splits > 1 && kWsFixedBytes + (size_t)plan.k_splits * a.M * a.N * sizeof(float) > a.workspace_bytes)
         plan = plan_stream_a16(a.M, a.N, a.K, false);
     const int mt = token_tiles(a.M);
     if (mt <= 1) return launch_stream_a16_t<1>(a, plan, st);

@@ -65,18 +65,15 @@ __device__ __forceinline__ void unpack8_nat(uint32_t p, uint32_t &d0, uint32_t &
     d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);   // lo2 hi2 lo3 hi3
 }
 
-// State of the in-kernel output quantization (QOUT = 1).  The tiles that share a band of token
-// rows publish the row maxima of their tile in g_row_max_slots, one 8-byte slot per (tile, row):
-// the float bits of max |g| below, the launch generation above.  A slot counts only if it carries
-// the generation of the running launch, so nothing is ever cleared; the last workgroup of a launch
-// to finish reading moves the generation on (the device does it, so replaying a captured launch
-// works).  Calls that quantize in the kernel must not overlap on one device: they share this state.
-constexpr int kMaxQuantSlots = 1 << 20;
+// In-kernel output quantization (QOUT = 1).  The tiles that share a band of token rows publish
+// the row maxima of their tile in the exchange slots of the caller's workspace, one 8-byte slot per
+// (tile, row): the float bits of max |g| below, a tag above.  The tag is the workspace's launch
+// generation plus one, so a slot counts only if the running launch wrote it and nothing is ever
+// cleared; the last workgroup of a launch to finish reading moves the generation on (the device does
+// it, so replaying a captured launch works).  The state lives in the workspace: calls on different
+// workspaces are independent, calls sharing one must be ordered on a stream.
 constexpr unsigned kQuantSpinLimit = 1u << 20;        // polls of ~1 us: about a second, far beyond any launch
-__device__ unsigned long long g_row_max_slots[kMaxQuantSlots];
-__device__ unsigned int g_quant_generation = 1;       // never 0: untouched slots read as generation 0
-__device__ unsigned int g_quant_done;                 // workgroups of the running launch that have read their band
-__device__ unsigned int g_quant_wait_expired;         // number of threads whose wait ran out
+constexpr unsigned kPoisonBits = 0x7fc00000u;         // a NaN; as an integer it is above the bits of every finite |g|
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE>
 struct TileCfg {
@@ -104,7 +101,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
     half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act,
-    int8_t *__restrict__ q_out, float *__restrict__ q_scale_out, int k_splits, int32_t *__restrict__ partial) {
+    int8_t *__restrict__ q_out, float *__restrict__ q_scale_out, int k_splits, int32_t *__restrict__ partial,
+    unsigned long long *__restrict__ q_slots, unsigned *__restrict__ q_ctl) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -460,9 +458,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr int LPR = WN * 2 / 16;          // lanes per output row (16 bytes each)
     static_assert((32 * LPR) % 64 == 0, "the 32-row block must be a whole number of store instructions");
     float rmax[FM];                           // QOUT: max |g| of this lane's token rows
-    unsigned gen = 0;                         // QOUT: generation of this launch, back before it is needed
+    unsigned gen_raw = 0;                     // QOUT: generation of this launch, back before it is needed
     if constexpr (QOUT == 1)
-        gen = __hip_atomic_load(&g_quant_generation, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        gen_raw = __hip_atomic_load(q_ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
         rmax[fm] = 0.0f;
@@ -541,18 +539,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             if (lc == 0) wave_max[wn * BM + wm * WM + fm * 32 + lr] = rmax[fm];
         }
         __syncthreads();
+        const unsigned tag = gen_raw + 1u;             // never 0: untouched slots carry tag 0
         if (tid < BM) {
             float a = wave_max[tid];
 #pragma unroll
             for (int w = 1; w < WAVES_N; ++w) a = fmaxf(a, wave_max[w * BM + tid]);
             // Publish this tile's maxima, then collect the band's: one store and, when the other
-            // tiles are already there, one round of loads.  The wait is bounded: a thread whose wait
-            // ran out goes on with what it has and counts itself in g_quant_wait_expired.
-            unsigned long long *band = g_row_max_slots + (size_t)tm * tiles_n * BM + tid;
-            __hip_atomic_store(band + (size_t)tn * BM, ((unsigned long long)gen << 32) | __float_as_uint(a),
+            // tiles are already there, one round of loads.  Maxima are compared as integers (the
+            // bits of non-negative floats order like the floats).  The wait is bounded.  A thread
+            // whose wait ran out counts itself in the control block, overwrites its slot with a
+            // NaN (tiles that arrive later then see it as the maximum) and takes NaN as the row
+            // maximum: its scale is NaN and its codes are -128, which the quantizer never produces.
+            unsigned long long *band = q_slots + (size_t)tm * tiles_n * BM + tid;
+            __hip_atomic_store(band + (size_t)tn * BM, ((unsigned long long)tag << 32) | __float_as_uint(a),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             constexpr int QB = 16;                     // slots fetched per round
             unsigned spins = 0;
+            unsigned abits = __float_as_uint(a);
             for (int j0 = 0; j0 < tiles_n; j0 += QB) {
                 while (true) {
                     unsigned long long v[QB];
@@ -562,25 +565,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                         v[u] = __hip_atomic_load(band + (size_t)j * BM, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                     bool all = true;
-                    float mx = a;
+                    unsigned mx = abits;
 #pragma unroll
                     for (int u = 0; u < QB; ++u) {
-                        all = all && (unsigned)(v[u] >> 32) == gen;
-                        mx = fmaxf(mx, __uint_as_float((unsigned)v[u]));
+                        all = all && (unsigned)(v[u] >> 32) == tag;
+                        const unsigned b = (unsigned)v[u];
+                        mx = b > mx ? b : mx;
                     }
                     if (all) {
-                        a = mx;
+                        abits = mx;
                         break;
                     }
                     if (++spins > kQuantSpinLimit) {
-                        __hip_atomic_fetch_add(&g_quant_wait_expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_fetch_add(q_ctl + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(band + (size_t)tn * BM, ((unsigned long long)tag << 32) | kPoisonBits,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        abits = kPoisonBits;
                         break;
                     }
                     __builtin_amdgcn_s_sleep(2);
                 }
+                if (abits >= kPoisonBits) break;
             }
             float scale, inv;
-            quant_scales(a, 127.0f, scale, inv);
+            if (abits >= kPoisonBits) {
+                scale = __uint_as_float(kPoisonBits);
+                inv = __uint_as_float(kPoisonBits);
+            } else {
+                quant_scales(__uint_as_float(abits), 127.0f, scale, inv);
+            }
             row_inv[tid] = inv;
             if (tn == 0 && m0 + tid < M) q_scale_out[m0 + tid] = scale;
         }
@@ -589,7 +602,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         // workgroup that completes it ends the launch's generation (below).
         unsigned done_before = 0;
         if (tid == 0)
-            done_before = __hip_atomic_fetch_add(&g_quant_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            done_before = __hip_atomic_fetch_add(q_ctl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // Codes: four consecutive columns per lane -> one dword of the BM x BN code tile in LDS (the
         // stage ring is free now), 16-byte chunks XOR-swizzled by row so that the 32 rows of a
         // fragment hit different banks; then every row leaves as one contiguous segment.
@@ -599,16 +612,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         for (int fm = 0; fm < FM; ++fm) {
             const int row = wm * WM + fm * 32 + lr;
             const float inv = row_inv[row];
+            const bool poisoned = __float_as_uint(inv) == kPoisonBits;   // the wait of this row ran out
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = wn * WN + fn * 32 + 8 * q + 4 * lc;
-                    const uint32_t d = pack4_code_bits(
+                    uint32_t d = pack4_code_bits(
                         quant_code_bits(__int_as_float(acc[fn][fm][4 * q]), inv),
                         quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 1]), inv),
                         quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 2]), inv),
                         quant_code_bits(__int_as_float(acc[fn][fm][4 * q + 3]), inv));
+                    if (poisoned) d = 0x80808080u;
                     *reinterpret_cast<uint32_t *>(ct + row * BN + (((col / 16) ^ (row & (QCH - 1))) * 16) + col % 16) = d;
                 }
             }
@@ -621,10 +636,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             if (m < M && n < N) *reinterpret_cast<int32x4 *>(q_out + (size_t)m * N + n) = v;
         }
         if (tid == 0 && done_before == gridDim.x - 1u) {
-            __hip_atomic_store(&g_quant_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned next = gen + 1u;
-            __hip_atomic_store(&g_quant_generation, next != 0u ? next : 1u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(q_ctl + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned next = gen_raw + 1u;        // the tag, next + 1, must never be 0
+            __hip_atomic_store(q_ctl, next != 0xffffffffu ? next : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 #endif
@@ -648,7 +662,8 @@ hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st, int k_splits = 1) {
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
                        a.acc_out, tiles_m, tiles_n, a.act, a.q_out, a.q_scale_out, k_splits,
-                       reinterpret_cast<int32_t *>(a.workspace));
+                       KSPLIT ? reinterpret_cast<int32_t *>(ws_partials(a.workspace)) : nullptr,
+                       QOUT ? ws_slots(a.workspace) : nullptr, QOUT ? ws_control(a.workspace) : nullptr);
     return hipGetLastError();
 }
 
@@ -742,9 +757,7 @@ int quant_tile_edge(int M, int N) {
 
 // block: 256 = 256x256 tile, eight waves; 256192 = 256x192 tile, eight waves (4 x 2, wave tile 64 x 96);
 //        192 = 256x128 tile, four waves, two workgroups per CU;
-//        128 = 128x128 tile: with at most one and a half tiles per CU, eight waves on a deep ring of
-//        128-byte stages (half the barriers per K, two waves per SIMD; measured 10-16 % faster there),
-//        otherwise four waves and 64 KB of LDS so that two workgroups share a CU.
+//        128 = 128x128 tile, eight waves on a deep ring of 128-byte stages (two waves per SIMD).
 hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     if (block == 256) {
         if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8>(a, st);
@@ -758,18 +771,13 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
         if (a.w_bits == 8) return launch_tile_t<256, 128, 2, 2, 64, 3, 8>(a, st);
         return launch_tile_t<256, 128, 2, 2, 64, 3, 4>(a, st);
     }
-    const long tiles = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (tiles <= 384) {
-        if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 4, 128, 4, 8>(a, st);
-        return launch_tile_t<128, 128, 2, 4, 128, 4, 4>(a, st);
-    }
-    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 64, 4, 8>(a, st);
-    return launch_tile_t<128, 128, 2, 2, 64, 4, 4>(a, st);
+    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 4, 128, 4, 8>(a, st);
+    return launch_tile_t<128, 128, 2, 4, 128, 4, 4>(a, st);
 }
 
 // The 128x128-tile schedule with K split over workgroups and a second kernel for the epilogue: for
 // token counts above the streaming schedules' whose tiles would occupy less than half the chip.
-// a.workspace holds the partial products, tile_split_workspace() bytes.
+// The partial products go to the partial-sum part of a.workspace (gemm_tile_split_workspace() bytes in all).
 int gemm_tile_splits(int M, int N, int K) {
     // the streaming schedules keep up to 64 tokens, and up to 128 where K is short (measured at 72 to 128
     // tokens, K split against streaming: 4096x4096 15.2 vs 17 us, 1024x4096 11.3 vs 13 us, 2048x2048 a tie)
@@ -779,7 +787,7 @@ int gemm_tile_splits(int M, int N, int K) {
 
 size_t gemm_tile_split_workspace(int M, int N, int K) {
     const int ks = gemm_tile_splits(M, N, K);
-    return ks > 1 ? (size_t)ks * M * N * sizeof(int32_t) : 0;
+    return ks > 1 ? kWsFixedBytes + (size_t)ks * M * N * sizeof(int32_t) : 0;
 }
 
 namespace {
@@ -789,7 +797,8 @@ hipError_t launch_splitk_finish(const GemmArgs &a, int k_splits, hipStream_t st)
     long blocks = (total + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL((splitk_finish_kernel<XT>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       reinterpret_cast<const int32x4 *>(a.workspace), k_splits, a.s_tok, a.s_w, a.N / a.groups,
+                       reinterpret_cast<const int32x4 *>(ws_partials(a.workspace)), k_splits, a.s_tok, a.s_w,
+                       a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, reinterpret_cast<half4 *>(a.out),
                        reinterpret_cast<int32x4 *>(a.acc_out), a.act, a.w_bits == 4 ? 4 : 0);
     return hipGetLastError();
@@ -798,7 +807,8 @@ hipError_t launch_splitk_finish(const GemmArgs &a, int k_splits, hipStream_t st)
 
 hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st) {
     const int ks = gemm_tile_splits(a.M, a.N, a.K);
-    if (ks < 2 || a.workspace == nullptr || a.workspace_bytes < (size_t)ks * a.M * a.N * sizeof(int32_t))
+    if (ks < 2 || a.workspace == nullptr ||
+        a.workspace_bytes < kWsFixedBytes + (size_t)ks * a.M * a.N * sizeof(int32_t))
         return hipErrorInvalidValue;
     hipError_t e = (a.w_bits == 8) ? launch_tile_t<128, 128, 2, 4, 128, 4, 8, 0, 0, 1>(a, st, ks)
                                    : launch_tile_t<128, 128, 2, 4, 128, 4, 4, 0, 0, 1>(a, st, ks);
@@ -807,16 +817,22 @@ hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st) {
 }
 
 // The tiled GeMM with the token-wise quantization of its output inside the kernel (a.q_out,
-// a.q_scale_out; a.out optional).  The tiles of a band of token rows wait for each other, so a band
-// must fit on the chip several times over, and every (tile, row) needs a slot of the exchange array.
-bool gemm_tile_quant_supported(int M, int N) {
+// a.q_scale_out; a.out optional).  The tiles of a band of token rows wait for each other.  Workgroups
+// are started in id order and the tiles of a band have consecutive ids, so the oldest unfinished band
+// of a launch has all its tiles running as soon as the launch holds a band's worth of compute units
+// (one workgroup of these kernels occupies a compute unit); a band is therefore limited to a quarter
+// of the compute units the device reports, which also leaves room for up to four such launches side
+// by side on different streams.  Every (tile, row) needs an exchange slot of the workspace.
+bool gemm_tile_quant_supported(int M, int N, size_t workspace_bytes) {
+    if (workspace_bytes < kWsFixedBytes) return false;
     const int edge = quant_tile_edge(M, N);
     const int tiles_m = (M + edge - 1) / edge, tiles_n = (N + edge - 1) / edge;
-    return tiles_n <= 64 && (long)tiles_m * tiles_n * edge <= kMaxQuantSlots;
+    return tiles_n <= compute_units() / 4 && (long)tiles_m * tiles_n * edge <= kMaxQuantSlots;
 }
 
 hipError_t launch_gemm_tile_quant(const GemmArgs &a, hipStream_t st) {
-    if (!gemm_tile_quant_supported(a.M, a.N) || a.q_out == nullptr || a.q_scale_out == nullptr)
+    if (a.workspace == nullptr || !gemm_tile_quant_supported(a.M, a.N, a.workspace_bytes) || a.q_out == nullptr ||
+        a.q_scale_out == nullptr)
         return hipErrorInvalidValue;
     if (quant_tile_edge(a.M, a.N) == 256) {
         if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 0, 1>(a, st);
@@ -826,13 +842,34 @@ hipError_t launch_gemm_tile_quant(const GemmArgs &a, hipStream_t st) {
     return launch_tile_t<128, 128, 2, 4, 128, 4, 4, 0, 1>(a, st);
 }
 
-// Number of workgroups whose bounded wait for their band ran out since the last call (0 in any
-// correct run); synchronises the device.
-hipError_t quant_wait_expired(unsigned *count) {
-    unsigned zero = 0;
-    hipError_t e = hipMemcpyFromSymbol(count, HIP_SYMBOL(g_quant_wait_expired), sizeof(unsigned));
-    if (e != hipSuccess) return e;
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_quant_wait_expired), &zero, sizeof(unsigned));
+// Compute units of the current device, asked once per device; 256 if no device answers.
+int compute_units() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    std::atomic<int> &slot = cached[dev & 63];
+    int v = slot.load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    slot.store(v, std::memory_order_relaxed);
+    return v;
+}
+
+// Zeroes the control words, the arrival counters and the exchange slots of a workspace.
+__global__ __launch_bounds__(256) void workspace_fill_kernel(int32x4 *p, long n) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = int32x4{0, 0, 0, 0};
+}
+
+hipError_t launch_workspace_init(void *ws, hipStream_t st) {
+    const long n = (long)(kWsFixedBytes / 16);
+    hipLaunchKernelGGL(workspace_fill_kernel, dim3(1024), dim3(256), 0, st, reinterpret_cast<int32x4 *>(ws), n);
+    return hipGetLastError();
 }
 
 // K splits of the FP16-activation call on the tiled schedule (1: none) and the workspace they need.
@@ -840,7 +877,7 @@ int gemm_a16_tile_splits(int M, int N, int K) { return tile_splits(M, N, K, 2); 
 
 size_t gemm_a16_tile_split_workspace(int M, int N, int K) {
     const int ks = tile_splits(M, N, K, 2);
-    return ks > 1 ? (size_t)ks * M * N * sizeof(float) : 0;
+    return ks > 1 ? kWsFixedBytes + (size_t)ks * M * N * sizeof(float) : 0;
 }
 
 // FP16 activations x INT8 weights on the tiled schedules.  The argument block is the
@@ -854,7 +891,8 @@ hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
     a.workspace = a16.workspace; a.workspace_bytes = a16.workspace_bytes; a.w_bits = 8; a.act = 0;
     // few tiles against a long K: split K (fp32 partials, added in split order by the second kernel)
     const int ks = tile_splits(a.M, a.N, a.K, 2);
-    if (ks > 1 && a.workspace != nullptr && a.workspace_bytes >= (size_t)ks * a.M * a.N * sizeof(float)) {
+    if (ks > 1 && a.workspace != nullptr &&
+        a.workspace_bytes >= kWsFixedBytes + (size_t)ks * a.M * a.N * sizeof(float)) {
         if (hipError_t e = launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1, 0, 1>(a, st, ks); e != hipSuccess) return e;
         return launch_splitk_finish<1>(a, ks, st);
     }

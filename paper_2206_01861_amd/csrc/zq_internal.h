@@ -23,6 +23,36 @@ inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, std::atom
     return hipSuccess;
 }
 
+// Layout of a GeMM workspace (device memory the caller owns and zq_workspace_init() has zeroed):
+//   [0, 256)            control words: [0] generation of the in-kernel output quantization,
+//                       [1] workgroups of the running launch that have read their band,
+//                       [2] threads whose bounded wait ran out
+//   [256, +32 KB)       arrival counters of the strips a streaming schedule splits along K
+//   [.., +4 MB)         exchange slots of the in-kernel output quantization (8 bytes per tile and row)
+//   [kWsFixedBytes, ..) partial sums of the K-split schedules
+// Every kernel leaves the first three parts ready for the next call; the parts never overlap, so
+// calls of any kind and shape can share a workspace as long as they are ordered on one stream.
+constexpr size_t kWsControlBytes = 256;
+constexpr int kMaxSharedStrips = 8192;
+constexpr int kMaxQuantSlots = 1 << 19;
+constexpr size_t kWsCountersOffset = kWsControlBytes;
+constexpr size_t kWsSlotsOffset = kWsCountersOffset + (size_t)kMaxSharedStrips * 4;
+constexpr size_t kWsFixedBytes = kWsSlotsOffset + (size_t)kMaxQuantSlots * 8;
+static_assert(kWsFixedBytes % 256 == 0, "the partial sums start on a 256-byte boundary");
+
+inline unsigned *ws_control(void *ws) { return reinterpret_cast<unsigned *>(ws); }
+inline unsigned *ws_counters(void *ws) { return reinterpret_cast<unsigned *>(static_cast<char *>(ws) + kWsCountersOffset); }
+inline unsigned long long *ws_slots(void *ws) {
+    return reinterpret_cast<unsigned long long *>(static_cast<char *>(ws) + kWsSlotsOffset);
+}
+inline void *ws_partials(void *ws) { return static_cast<char *>(ws) + kWsFixedBytes; }
+
+// Compute units of the current device (256 when no device answers: the host-only queries still work).
+int compute_units();
+
+// Zero the fixed part of a workspace (a fill kernel, so the call may be captured into a graph).
+hipError_t launch_workspace_init(void *ws, hipStream_t st);
+
 enum RowOp { kOpLayerNorm = 0, kOpGeluErf = 1, kOpGeluTanh = 2, kOpIdentity = 3 };
 
 // in fp16 [M,K]; p0 = gamma (LayerNorm) or bias (GeLU, nullable); p1 = beta (nullable).
@@ -39,7 +69,7 @@ hipError_t launch_weight_quant(const void *w, int N, int K, int groups, int bits
 // GeMM schedules.  The order is part of the test/tuning hook of the C ABI.
 enum GemmVariant {
     kGemmSimple = 0,      // one wave per 16x16 tile, operands from global; any legal shape
-    kGemmTile128 = 1,     // 128x128 block tile, eight or four waves by tile count
+    kGemmTile128 = 1,     // 128x128 block tile, eight waves
     kGemmTile256 = 2,     // 256x256 block tile, eight waves
     kGemmSkinny = 3,      // M <= 128, K % 256 == 0: weight streaming, whole K in one workgroup
     kGemmSkinnySplitK = 4,// same, K also split across workgroups (needs workspace)
@@ -73,10 +103,10 @@ int gemm_tile_splits(int M, int N, int K);
 size_t gemm_tile_split_workspace(int M, int N, int K);
 hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st);
 
-// Tiled GeMM that also quantizes its output rows token-wise inside the kernel (out may be null).
-bool gemm_tile_quant_supported(int M, int N);
+// Tiled GeMM that also quantizes its output rows token-wise inside the kernel (out may be null);
+// needs a workspace of at least kWsFixedBytes.
+bool gemm_tile_quant_supported(int M, int N, size_t workspace_bytes);
 hipError_t launch_gemm_tile_quant(const GemmArgs &a, hipStream_t st);
-hipError_t quant_wait_expired(unsigned *count);
 
 // A caller-supplied cut of the streaming schedules for this shape, if one was registered.
 bool tuned_stream_plan(int M, int N, int K, int w_bits, int *row_blocks, int *k_splits);

@@ -12,6 +12,13 @@ from paper_2206_01861_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 P = 0x10000  # a non-NULL, 16-byte aligned fake device address; never dereferenced on an error path
 OK, E_NULL, E_SHAPE, E_ALIGN, E_UNSUP = 0, 1, 2, 3, 4
+FIXED = zq.WORKSPACE_FIXED_BYTES   # control words, arrival counters and exchange slots in front of the partial sums
+
+
+def test_workspace_constant_matches_the_header():
+    text = open(os.path.join(ROOT, "include", "zq.h")).read()
+    assert int(re.search(r"#define ZQ_WORKSPACE_FIXED_BYTES (\d+)", text).group(1)) == FIXED
+    assert FIXED == 256 + 8192 * 4 + (1 << 19) * 8
 
 
 def _declared():
@@ -48,7 +55,7 @@ def test_variant_table():
     assert zq.gemm_variant_name(zq.gemm_choose_variant(128, 768, 784)) == "simple"   # tiny: untiled
     assert zq.gemm_variant_name(zq.gemm_choose_variant(4096, 768, 784)).startswith("tile")   # ragged K is tiled too
     ws = zq.gemm_workspace_bytes(64, 6144, 24576)
-    assert ws > 0 and ws % (64 * 6144 * 4) == 0
+    assert ws > FIXED and (ws - FIXED) % (64 * 6144 * 4) == 0
     assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws)) == "skinny_splitk"
     assert zq.gemm_variant_name(zq.gemm_choose_variant(64, 6144, 24576, 8, ws - 1)) == "skinny"
     assert zq.gemm_workspace_bytes(4096, 4096, 1024) == 0
@@ -155,6 +162,13 @@ def test_gemm_validation(fname, kmul):
     assert call(groups=8) == E_SHAPE               # 8 columns per group
     assert call(K=128 + kmul // 2) == E_SHAPE
     assert call(K=133152) == E_SHAPE               # INT32 accumulator could wrap
+    if kmul == 32:                                 # INT4 codes travel as code * 16 and -8 is legal: K * 127 * 128 < 2^31
+        assert call(K=132128) == E_SHAPE
+        prev = zq.force_gemm_variant(3)
+        try:
+            assert call(K=132064) == E_UNSUP       # inside the bound: refused only by the forced schedule, nothing launched
+        finally:
+            zq.force_gemm_variant(prev)
     assert call(M=65536, K=32768) == E_SHAPE       # an operand of 2 GiB: beyond the 32-bit buffer offsets
     assert call(N=65536 * (2 if kmul == 32 else 1), K=32768, groups=64) == E_SHAPE
     assert call(bias=P + 2) == E_ALIGN
@@ -190,9 +204,13 @@ def test_where_the_output_is_quantized():
     """Tiled schedules quantize in the GeMM kernel, within the limits of the exchange arrays and of
     the band that must be resident at once; the debug switch turns it off."""
     q = zq.gemm_quantizes_in_kernel
+    def q(M, N, K, bits, ws=FIXED):
+        return zq.gemm_quantizes_in_kernel(M, N, K, bits, ws)
+
     assert q(4096, 4096, 1024, 8) and q(4096, 4096, 1024, 4) and q(16384, 6144, 24576, 8)
-    assert q(65536, 4096, 64, 8) and not q(65537, 4096, 64, 8)            # slots of the exchange array
-    assert q(4096, 16384, 4096, 8) and not q(4096, 16384 + 256, 4096, 8)  # tiles per band
+    assert not q(4096, 4096, 1024, 8, 0) and not q(4096, 4096, 1024, 8, FIXED - 1)   # the exchange lives in the workspace
+    assert q(32768, 4096, 64, 8) and not q(32769, 4096, 64, 8)            # exchange slots of a workspace
+    assert q(4096, 16384, 4096, 8) and not q(4096, 16384 + 256, 4096, 8)  # tiles per band: a quarter of 256 compute units
     assert not q(64, 4096, 4096, 8) and not q(1, 16, 16, 8)               # streaming / untiled schedules
     assert not q(0, 16, 16, 8) and not q(16, 16, 16, 5)
     prev = zq.set_in_kernel_quant(False)
@@ -201,7 +219,24 @@ def test_where_the_output_is_quantized():
     finally:
         assert zq.set_in_kernel_quant(prev) is False
     assert q(4096, 4096, 1024, 8)
-    assert zq.lib().zq_quant_wait_expired(None) == E_NULL
+    # the size query for calls with quantized output: the fixed part where the kernel quantizes, and never
+    # less than the plain call's
+    assert zq.gemm_quant_workspace_bytes(4096, 4096, 1024, 8) == FIXED and zq.gemm_workspace_bytes(4096, 4096, 1024, 8) == 0
+    assert zq.gemm_quant_workspace_bytes(8, 256, 256, 8) == 0
+    assert zq.gemm_quant_workspace_bytes(32, 2048, 8192, 8) == zq.gemm_workspace_bytes(32, 2048, 8192, 8) > FIXED
+    assert zq.gemm_quant_workspace_bytes(192, 4096, 4096, 8) == zq.gemm_workspace_bytes(192, 4096, 4096, 8)
+    c = ctypes.c_int(0)
+    assert zq.lib().zq_quant_wait_expired(None, ctypes.byref(c)) == E_NULL
+    assert zq.lib().zq_quant_wait_expired(P, None) == E_NULL
+    assert zq.lib().zq_quant_wait_expired(P + 4, ctypes.byref(c)) == E_ALIGN
+
+
+def test_workspace_init_validation():
+    f = zq.lib().zq_workspace_init
+    assert f(None, FIXED, None) == E_NULL
+    assert f(P, FIXED - 1, None) == E_SHAPE
+    assert f(P, 0, None) == E_SHAPE
+    assert f(P + 8, FIXED, None) == E_ALIGN
 
 
 def test_standalone_quantizer_and_dequantizer_validation():
@@ -234,7 +269,7 @@ def test_tuning_table_overrides_the_choice():
         # a streaming cut with a K split: the workspace query and the plan follow it
         zq.tune_set(1, 32, N, K, 8, 4, 64, 4)
         ws = zq.gemm_workspace_bytes(M, N, K, 8)
-        assert ws == 4 * M * N * 4
+        assert ws == FIXED + 4 * M * N * 4
         assert zq.gemm_stream_plan(M, N, K, 8, ws) == (64, 4, 4)
         assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws)) == "skinny_splitk"
         assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, 0)) == "skinny"   # no workspace: entry ignored
@@ -260,7 +295,7 @@ def test_tile_k_split_dispatch():
     half the chip splits K when the workspace holds the partial products, and only then."""
     for (M, N, K) in [(192, 4096, 4096), (300, 2048, 8192), (130, 4096, 4000), (96, 1040, 3968)]:
         ws = zq.gemm_workspace_bytes(M, N, K, 8)
-        assert ws > 0 and ws % (M * N * 4) == 0 and 2 <= ws // (M * N * 4) <= 16
+        assert ws > FIXED and (ws - FIXED) % (M * N * 4) == 0 and 2 <= (ws - FIXED) // (M * N * 4) <= 16
         assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws)) == "tile128_splitk"
         assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, ws - 1)) != "tile128_splitk"
         assert zq.gemm_workspace_bytes(M, N, K, 4) == ws            # the INT4 call splits alike
@@ -297,15 +332,15 @@ def test_w8a16_workspace_and_plan():
         ws = zq.gemm_w8a16_workspace_bytes(M, N, K)
         rb, ks, c = zq.gemm_w8a16_stream_plan(M, N, K, ws)
         assert 1 <= rb <= N // 16 and 1 <= c <= 8 and c == -(-(N // 16) // rb)
-        assert ws == (ks * M * N * 4 if ks > 1 else 0)
+        assert ws == (FIXED + ks * M * N * 4 if ks > 1 else 0)
         assert zq.gemm_w8a16_stream_plan(M, N, K, 0)[1] == 1
     # 65 to 128 tokens: at least what the 64-token streaming launches need, more where the tiled schedule
     # with a K split is the faster choice
     assert zq.gemm_w8a16_workspace_bytes(100, 2048, 8192) >= zq.gemm_w8a16_workspace_bytes(64, 2048, 8192) > 0
     assert zq.gemm_w8a16_workspace_bytes(100, 18432, 6144) == zq.gemm_w8a16_workspace_bytes(64, 18432, 6144)
     # above 128 tokens: the tiled schedule, which splits K where its tiles would leave most of the chip idle
-    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) % (129 * 2048 * 4) == 0
-    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) >= 2 * 129 * 2048 * 4
+    assert (zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) - FIXED) % (129 * 2048 * 4) == 0
+    assert zq.gemm_w8a16_workspace_bytes(129, 2048, 8192) >= FIXED + 2 * 129 * 2048 * 4
     assert zq.gemm_w8a16_workspace_bytes(4096, 4096, 4096) == 0
     assert zq.gemm_w8a16_workspace_bytes(16, 2048, 1000) == 0       # K not a multiple of 256: untiled
     with pytest.raises(zq.ZQError):

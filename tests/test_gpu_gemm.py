@@ -66,6 +66,9 @@ SHAPES = [
     (SIMPLE, 1, 16, 16, 1), (SIMPLE, 7, 48, 80, 3), (SIMPLE, 17, 768, 784, 48), (SIMPLE, 129, 96, 1024, 2),
     (TILE128, 128, 768, 768, 48), (TILE128, 129, 272, 256, 17), (TILE128, 300, 400, 384, 25),
     (TILE128, 1, 16, 128, 1), (TILE128, 515, 1024, 1024, 64),
+    # more 128x128 tiles than compute units (21 x 21, ragged in M, N and K): the ring refills many times and
+    # later tiles start as earlier ones leave
+    (TILE128, 2600, 2576, 544, 161), (TILE128, 2600, 2576, 1024, 161),
     (TILE256, 256, 256, 128, 16), (TILE256, 300, 528, 512, 33), (TILE256, 1030, 768, 256, 48),
     (TILE256, 17, 16, 384, 1),
     # K that is not a multiple of the stage depth: the last stage is zero filled
@@ -114,7 +117,7 @@ def test_gemm_against_oracle(zq, orc, bits, variant, M, N, K, g):
         nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
         if nbytes == 0:
             pytest.skip("shape does not split")
-        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        ws = zq.new_workspace(nbytes)
     if variant == SKINNY and bits == 8 and M <= 32 and K >= 4096:
         assert zq.gemm_stream_k_ranges(M, N, K, bits, 0) == 2
     res = _run(zq, bits, variant, xq, s_tok, wq, s_w, bias, workspace=ws)
@@ -152,7 +155,7 @@ def test_largest_k_fills_the_accumulator(zq, orc):
         assert np.abs(want).max() < 2 ** 31
         for variant in variants:
             nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
-            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+            ws = zq.new_workspace(nbytes)
             res = _run(zq, 8, variant, xq, s_tok, wq, s_w, None, workspace=ws)
             assert np.array_equal(host(res[1]).astype(np.int64), want), (K, variant)
             ref, mag = orc.dequant(want.astype(np.int32), s_tok, s_w, None)
@@ -176,7 +179,7 @@ def test_dispatch_and_determinism(zq, orc):
                          (100, 4096, 2048, 64)]:
         xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
         nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
-        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        ws = zq.new_workspace(nbytes)
         r1 = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
         r2 = _run(zq, 8, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
         _check(orc, r1, xq, s_tok, codes, s_w, bias, "auto %dx%dx%d" % (M, N, K))
@@ -220,19 +223,31 @@ def test_quantized_linear_end_to_end(zq, orc):
     assert rel < 0.05
 
 
-# Full-size workloads: sampled rows against the oracle plus the Freivalds identity on everything.
-FULL = [
-    ("c2_ffc1", 4096), ("c2_ffc2", 4096), ("c3_qkv", 2048), ("c3_ffc2", 32), ("c3_ffc1", 1),
-    ("c4_ffc1", 16), ("c4_ffc2", 1), ("c4_ffc1", 4096), ("c4_qkv", 16), ("c4_out", 1), ("c5_ffc2", 64), ("c5_qkv", 64),
-    ("c5_ffc1", 16384),
-]
+# Full-size workloads, every (linear, token count) of the workload table: sampled rows against the
+# oracle plus the Freivalds identity on every accumulator, in the launch configuration the benchmark times
+# (default dispatch, a workspace of the size the library asks for).
+FULL = [(name, M) for name in zq_inputs.LINEARS for M in zq_inputs.TOKENS[name.split("_")[0]]]
+assert len(FULL) == 37
 
 
 @pytest.mark.parametrize("name,M", FULL)
 def test_full_size_workloads(zq, orc, name, M):
-    print("full", name, M, flush=True)
     K, N, g, bits = zq_inputs.LINEARS[name]
+    nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
+    print("full", name, M, zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nbytes)), flush=True)
     _large_shape_check(zq, orc, name, M, N, K, g, bits, zq_inputs.rng_for(int(name[1]), M))
+
+
+# The re-quantization of the output (token-wise codes of the FP16 tensor for the next GeMM) at full
+# size: inside the tiled GeMM kernel at a prefill shape, by the second kernel behind the streaming
+# schedule at a decode shape.  Every code and scale against the oracle's quantizer on the GPU's FP16 rows.
+@pytest.mark.parametrize("name,M,in_kernel", [("c3_qkv", 2048, True), ("c5_qkv", 64, False), ("c2_ffc1", 4096, True)])
+def test_full_size_requantization(zq, orc, name, M, in_kernel):
+    K, N, g, bits = zq_inputs.LINEARS[name]
+    print("full requant", name, M, flush=True)
+    nbytes = zq.gemm_quant_workspace_bytes(M, N, K, bits)
+    assert bool(zq.gemm_quantizes_in_kernel(M, N, K, bits, nbytes)) == in_kernel
+    _large_shape_check(zq, orc, name, M, N, K, g, bits, zq_inputs.rng_for(int(name[1]), 9000 + M), requant=True)
 
 
 # Token counts between decode and prefill on the workload matrices: the schedules with a K split
@@ -248,9 +263,10 @@ def test_mid_token_counts_on_workload_matrices(zq, orc, name, M):
     _large_shape_check(zq, orc, name, M, N, K, g, bits, zq_inputs.rng_for(int(name[1]), 7000 + M))
 
 
-def _large_shape_check(zq, orc, name, M, N, K, g, bits, rng):
+def _large_shape_check(zq, orc, name, M, N, K, g, bits, rng, requant=False):
     """Sampled rows against the oracle, the Freivalds identity on every accumulator, and the FP16
-    output against the epilogue of the accumulators everywhere."""
+    output against the epilogue of the accumulators everywhere.  With requant also out_q / out_s_tok:
+    every row against the oracle's token-wise quantizer applied to the FP16 output."""
     g_t = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED + M)
     qmax = 127 if bits == 8 else 7
     xq_t = torch.randint(-127, 128, (M, K), generator=g_t, device="cuda", dtype=torch.int8)
@@ -263,11 +279,19 @@ def _large_shape_check(zq, orc, name, M, N, K, g, bits, rng):
     s_tok = zq_inputs.random_scales(rng, M, 5e-3, 0.3)
     s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-3)
     bias = zq_inputs.bias(rng, N, std=0.05)
-    nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    nbytes = zq.gemm_quant_workspace_bytes(M, N, K, bits) if requant else zq.gemm_workspace_bytes(M, N, K, bits)
+    ws = zq.new_workspace(nbytes)
     fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
-    out, acc, _, _ = fn(xq_t, dev(s_tok), wq_t, dev(s_w), dev(bias), want_acc=True, workspace=ws)
+    out, acc, out_q, out_s = fn(xq_t, dev(s_tok), wq_t, dev(s_w), dev(bias), want_acc=True, requant=requant,
+                                workspace=ws)
     torch.cuda.synchronize()
+    assert zq.quant_wait_expired(ws) == 0
+    if requant:
+        q_h, s_h, out_h = host(out_q), host(out_s), host(out)
+        for m0 in range(0, M, 512):
+            q_o, s_o = orc.quant_tokenwise(out_h[m0:m0 + 512].astype(np.float32))
+            assert_bit_equal(s_h[m0:m0 + 512], s_o, name + " out_s_tok")
+            assert_bit_equal(q_h[m0:m0 + 512], q_o, name + " out_q")
     freivalds_gpu(acc, xq_t, codes_t, seed=M + N)
     rows = np.unique(np.concatenate([[0, M - 1, M // 2], rng.integers(0, M, size=5),
                                      [min(M - 1, 255), min(M - 1, 256), min(M - 1, 127)]]))
@@ -304,7 +328,7 @@ def test_autotune_registers_a_runnable_schedule(zq, orc):
             assert len(results) >= 3 and entry["us"] == min(r["us"] for r in results)
             nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
             assert zq.gemm_choose_variant(M, N, K, bits, nbytes) == entry["variant"]
-            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+            ws = zq.new_workspace(nbytes)
             res = _run(zq, bits, -1, xq, s_tok, wq, s_w, bias, workspace=ws)
             _check(orc, res, xq, s_tok, codes, s_w, bias, "tuned %dx%dx%d" % (M, N, K))
         finally:
@@ -328,3 +352,63 @@ def test_two_k_ranges_with_four_strips_per_workgroup(zq, orc):
         _check(orc, res, xq, s_tok, codes, s_w, bias, "two ranges, four strips")
     finally:
         zq.tune_clear()
+
+
+def test_many_128_tiles_through_the_schedule_table(zq, orc):
+    """128x128 tiles on a shape the built-in choice gives to larger tiles, reached the way a caller would:
+    through an entry of the measured schedule table.  Twenty-one by twenty-one tiles, ragged everywhere."""
+    M, N, K, g = 2600, 2576, 1024, 161
+    rng = zq_inputs.rng_for(4, 91)
+    for bits in (8, 4):
+        xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, bits)
+        zq.tune_clear()
+        try:
+            assert zq.gemm_choose_variant(M, N, K, bits, 0) != TILE128
+            zq.tune_set(M, M, N, K, bits, TILE128)
+            assert zq.gemm_choose_variant(M, N, K, bits, 0) == TILE128
+            res = _run(zq, bits, -1, xq, s_tok, wq, s_w, bias)
+            _check(orc, res, xq, s_tok, codes, s_w, bias, "tuned tile128 %d-bit" % bits)
+        finally:
+            zq.tune_clear()
+
+
+def test_calls_on_two_streams_with_their_own_workspaces(zq, orc):
+    """What the kernels of a call exchange lives in the caller's workspace, so calls on different
+    workspaces may run at the same time: two K-split GeMMs and two GeMMs that quantize their output in
+    the kernel, issued alternately on two streams several times over, must all give the oracle's bits."""
+    rng = zq_inputs.rng_for(4, 92)
+    split = []
+    for (M, N, K, g) in [(32, 2048, 8192, 128), (16, 1040, 12288, 65)]:
+        xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+        nbytes = zq.gemm_workspace_bytes(M, N, K, 8)
+        assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, 8, nbytes)) == "skinny_splitk"
+        split.append(dict(a=(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias)), ws=zq.new_workspace(nbytes),
+                          h=(xq, s_tok, codes, s_w, bias), res=[]))
+    quant = []
+    for (M, N, K, g) in [(1024, 2048, 512, 64), (515, 1024, 1024, 64)]:
+        xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
+        ws = zq.new_workspace(zq.gemm_quant_workspace_bytes(M, N, K, 8))
+        assert zq.gemm_quantizes_in_kernel(M, N, K, 8, ws.numel())
+        quant.append(dict(a=(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias)), ws=ws,
+                          h=(xq, s_tok, codes, s_w, bias), res=[]))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(6):
+        for i in (0, 1):
+            with torch.cuda.stream(streams[i]):
+                split[i]["res"].append(zq.zq_gemm_i8_dequant(*split[i]["a"], want_acc=True, workspace=split[i]["ws"]))
+                quant[i]["res"].append(zq.zq_gemm_i8_dequant(*quant[i]["a"], want_acc=True, requant=True,
+                                                             workspace=quant[i]["ws"]))
+    torch.cuda.synchronize()
+    for c in split + quant:
+        xq, s_tok, codes, s_w, bias = c["h"]
+        acc_o = orc.matmul_i32(xq, codes)
+        ref, mag = orc.dequant(acc_o, s_tok, s_w, bias)
+        for rep, (out, acc, out_q, out_s) in enumerate(c["res"]):
+            assert_bit_equal(host(acc), acc_o, "two streams acc rep %d" % rep)
+            assert_out_close(host(out), ref, mag, "two streams out rep %d" % rep)
+            if out_q is not None:
+                q_o, s_o = orc.quant_tokenwise(host(out).astype(np.float32))
+                assert_bit_equal(host(out_s), s_o, "two streams out_s_tok rep %d" % rep)
+                assert_bit_equal(host(out_q), q_o, "two streams out_q rep %d" % rep)
+        assert zq.quant_wait_expired(c["ws"]) == 0

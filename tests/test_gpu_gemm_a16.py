@@ -56,7 +56,7 @@ def test_w8a16_against_oracle(zq, orc, M, N, K, g):
     s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-2)
     bias = zq_inputs.bias(rng, N)
     nbytes = zq.gemm_w8a16_workspace_bytes(M, N, K)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nbytes)
     out = zq.zq_gemm_w8a16_dequant(dev(x), dev(codes), dev(s_w), dev(bias), workspace=ws)
     out2 = zq.zq_gemm_w8a16_dequant(dev(x), dev(codes), dev(s_w), dev(bias), workspace=ws)
     torch.cuda.synchronize()
@@ -95,7 +95,7 @@ def test_w8a16_full_size_sampled_rows(zq, orc, name, M):
     s_w = (torch.rand(g, generator=gen, device="cuda") * 1e-3 + 1e-4)
     bias = (torch.randn(N, generator=gen, device="cuda") * 0.01).half()
     nbytes = zq.gemm_w8a16_workspace_bytes(M, N, K)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nbytes)
     out = zq.zq_gemm_w8a16_dequant(x, codes, s_w, bias, workspace=ws)
     torch.cuda.synchronize()
     rows = sorted(set([0, M - 1, M // 2, min(M - 1, 15), min(M - 1, 16), min(M - 1, 255), min(M - 1, 256)]))

@@ -52,7 +52,7 @@ def test_gemm_gelu_quant_against_oracle(zq, orc, variant, M, N, K, g, bits, appr
     nbytes = zq.gemm_workspace_bytes(M, N, K, bits)
     if variant in (SKINNY_SPLITK, 7) and nbytes == 0:
         pytest.skip("shape does not split")
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda") if variant in (SKINNY_SPLITK, 7, -1) else None
+    ws = zq.new_workspace(nbytes)
     if (variant, M) == (-1, 192):
         assert zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nbytes)) == "tile128_splitk"
         assert zq.gemm_quantizes_in_kernel(M, N, K, bits, nbytes) == 0
@@ -63,6 +63,7 @@ def test_gemm_gelu_quant_against_oracle(zq, orc, variant, M, N, K, g, bits, appr
         torch.cuda.synchronize()
     finally:
         zq.force_gemm_variant(prev)
+    assert zq.quant_wait_expired(ws) == 0
     _check_fused(orc, host(g16), host(gq), host(s), xq, s_tok, codes, s_w, bias, approx,
                  "fused %s %d-bit %dx%dx%d" % (zq.gemm_variant_name(variant), bits, M, N, K))
 
@@ -79,7 +80,8 @@ def test_fused_chain_tracks_two_call_chain(zq, orc):
     xq, st, _ = zq.zq_layernorm_quant_tokenwise(dev(x), dev(gamma), dev(beta), 1e-5)
     h, _, _, _ = zq.zq_gemm_i8_dequant(xq, st, wq1, sw1, dev(b1))
     hq, st2, _ = zq.zq_gelu_quant_tokenwise(h, None)
-    g16, gq, s = zq.zq_gemm_gelu_quant_tokenwise(xq, st, wq1, sw1, dev(b1))
+    ws = zq.new_workspace(zq.gemm_quant_workspace_bytes(M, F, H, 8))
+    g16, gq, s = zq.zq_gemm_gelu_quant_tokenwise(xq, st, wq1, sw1, dev(b1), workspace=ws)
     torch.cuda.synchronize()
     _check_fused(orc, host(g16), host(gq), host(s), host(xq), host(st), host(wq1), host(sw1), b1, False, "chain")
     rel_s = np.abs(host(s) - host(st2)) / host(st2)
@@ -112,24 +114,29 @@ def test_in_kernel_quantization_equals_second_kernel(zq, orc, M, N, K, g, bits):
     s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
     args = (dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias))
     gemm = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
+    ws = zq.new_workspace(0)                 # the fixed part is all the in-kernel quantization needs
+    wsb = ws.numel()
     # small problems go to the untiled schedule by themselves: put them on a tiled one
-    tiled = zq.gemm_choose_variant(M, N, K, bits) in (TILE128, TILE256)
+    tiled = zq.gemm_choose_variant(M, N, K, bits, wsb) in (TILE128, TILE256)
     prev_variant = zq.force_gemm_variant(-1 if tiled else TILE128)
     try:
-        assert zq.gemm_quantizes_in_kernel(M, N, K, bits)
+        assert zq.gemm_quantizes_in_kernel(M, N, K, bits, wsb)
+        assert not zq.gemm_quantizes_in_kernel(M, N, K, bits, 0)         # no workspace: the second kernel
+        if tiled:
+            assert zq.gemm_quant_workspace_bytes(M, N, K, bits) == wsb
+        g_ref, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)      # second-kernel path (no workspace)
         prev = zq.set_in_kernel_quant(False)
         try:
-            assert not zq.gemm_quantizes_in_kernel(M, N, K, bits)
-            g_ref, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)
-            o_ref, _, oq_ref, os_ref = gemm(*args, requant=True)
+            assert not zq.gemm_quantizes_in_kernel(M, N, K, bits, wsb)
+            o_ref, _, oq_ref, os_ref = gemm(*args, requant=True, workspace=ws)
             torch.cuda.synchronize()
         finally:
             zq.set_in_kernel_quant(prev)
         runs = []
         for rep in range(2):
-            g1, q1, s1 = zq.zq_gemm_gelu_quant_tokenwise(*args)
-            g2, q2, s2 = zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False)
-            o3, _, q3, s3 = gemm(*args, requant=True)
+            g1, q1, s1 = zq.zq_gemm_gelu_quant_tokenwise(*args, workspace=ws)
+            g2, q2, s2 = zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False, workspace=ws)
+            o3, _, q3, s3 = gemm(*args, requant=True, workspace=ws)
             torch.cuda.synchronize()
             runs.append((g1, q1, s1, g2, q2, s2, o3, q3, s3))
     finally:
@@ -144,7 +151,7 @@ def test_in_kernel_quantization_equals_second_kernel(zq, orc, M, N, K, g, bits):
         assert_bit_equal(host(o3), host(o_ref), "plain GeMM out rep %d" % rep)
         assert_bit_equal(host(s3), host(os_ref), "plain GeMM out_s_tok rep %d" % rep)
         assert_bit_equal(host(q3), host(oq_ref), "plain GeMM out_q rep %d" % rep)
-    assert zq.quant_wait_expired() == 0
+    assert zq.quant_wait_expired(ws) == 0
     rows = sorted(set([0, M - 1, M // 2, min(M - 1, 127), min(M - 1, 128), min(M - 1, 255), min(M - 1, 256)]))
     _check_fused(orc, host(g1)[rows], host(q1)[rows], host(s1)[rows], xq[rows], s_tok[rows], codes, s_w, bias, False,
                  "in-kernel %d-bit %dx%dx%d" % (bits, M, N, K))
@@ -169,7 +176,9 @@ def test_in_kernel_quantization_under_graph_replay(zq, orc):
     be replayed: every replay, with new inputs copied into the captured buffers and eager calls of
     other shapes in between, must give the bits of the two-kernel path on the same inputs."""
     M, N, K, g = 1024, 2048, 512, 64
-    assert zq.gemm_quantizes_in_kernel(M, N, K, 8)
+    ws = zq.new_workspace(0)
+    ws2 = zq.new_workspace(0)                # the eager calls between the replays use their own
+    assert zq.gemm_quantizes_in_kernel(M, N, K, 8, ws.numel())
     rng = zq_inputs.rng_for(8, 1)
     _, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
     s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
@@ -179,11 +188,12 @@ def test_in_kernel_quantization_under_graph_replay(zq, orc):
     s2 = torch.empty(M, dtype=torch.float32, device="cuda")
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False)
+        zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False, workspace=ws)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
-            zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False)
+            zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d, out=(None, gq, s2), keep_g=False,
+                                            workspace=ws)
     torch.cuda.synchronize()
     other = _case(zq_inputs.rng_for(8, 2), 300, 400, 384, 25, 8)
     for rep in range(4):
@@ -198,18 +208,18 @@ def test_in_kernel_quantization_under_graph_replay(zq, orc):
         # eager work of another shape between the replays, on the in-kernel path as well
         prev_v = zq.force_gemm_variant(TILE128)
         try:
-            zq.zq_gemm_gelu_quant_tokenwise(dev(other[0]), dev(other[1]), dev(other[5]), dev(other[2]), dev(other[3]))
+            zq.zq_gemm_gelu_quant_tokenwise(dev(other[0]), dev(other[1]), dev(other[5]), dev(other[2]), dev(other[3]),
+                                            workspace=ws2 if rep % 2 else ws)
         finally:
             zq.force_gemm_variant(prev_v)
-        prev = zq.set_in_kernel_quant(False)
-        try:
-            _, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d)
-            torch.cuda.synchronize()
-        finally:
-            zq.set_in_kernel_quant(prev)
+        g_ref, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(xq_d, st_d, wq_d, sw_d, b_d)   # second-kernel path
+        torch.cuda.synchronize()
         assert_bit_equal(got_s, host(s_ref), "replay %d s_tok" % rep)
         assert_bit_equal(got_q, host(q_ref), "replay %d codes" % rep)
-    assert zq.quant_wait_expired() == 0
+        if rep == 0:                         # and the replayed bits are the oracle's, given the FP16 tensor
+            _check_fused(orc, host(g_ref)[:64], got_q[:64], got_s[:64], xq[:64], s_tok[:64], codes, s_w, bias, False,
+                         "replayed in-kernel quantization")
+    assert zq.quant_wait_expired(ws) == 0 and zq.quant_wait_expired(ws2) == 0
 
 
 def test_in_kernel_quantization_while_another_stream_keeps_the_chip_busy(zq, orc):
@@ -221,13 +231,10 @@ def test_in_kernel_quantization_while_another_stream_keeps_the_chip_busy(zq, orc
     xq, s_tok, s_w, bias, codes, wq = _case(rng, M, N, K, g, 8)
     s_tok = (s_tok * (3.0 / max(1e-9, float(np.sqrt(K)) * 40.0 * float(s_tok.mean()) * float(s_w.mean())))).astype(np.float32)
     args = (dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias))
-    assert zq.gemm_quantizes_in_kernel(M, N, K, 8)
-    prev = zq.set_in_kernel_quant(False)
-    try:
-        _, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)
-        torch.cuda.synchronize()
-    finally:
-        zq.set_in_kernel_quant(prev)
+    ws = zq.new_workspace(0)
+    assert zq.gemm_quantizes_in_kernel(M, N, K, 8, ws.numel())
+    _, q_ref, s_ref = zq.zq_gemm_gelu_quant_tokenwise(*args)             # second-kernel path
+    torch.cuda.synchronize()
     a = torch.randn((4096, 4096), device="cuda", dtype=torch.float16)
     side = torch.cuda.Stream()
     outs = []
@@ -235,9 +242,9 @@ def test_in_kernel_quantization_while_another_stream_keeps_the_chip_busy(zq, orc
         for _ in range(40):
             b = a @ a                                   # ~0.1 ms each on the other stream
     for _ in range(12):
-        outs.append(zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False))
+        outs.append(zq.zq_gemm_gelu_quant_tokenwise(*args, keep_g=False, workspace=ws))
     torch.cuda.synchronize()
-    assert zq.quant_wait_expired() == 0
+    assert zq.quant_wait_expired(ws) == 0
     for i, (_, q, s) in enumerate(outs):
         assert_bit_equal(host(s), host(s_ref), "call %d s_tok" % i)
         assert_bit_equal(host(q), host(q_ref), "call %d codes" % i)

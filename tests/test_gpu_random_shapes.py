@@ -60,7 +60,7 @@ def test_default_dispatch_against_oracle(zq, orc, bits, M, N, K, g):
     else:
         u = codes.astype(np.uint8) & 0xF
         wq = (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nbytes)
     fn = zq.zq_gemm_i8_dequant if bits == 8 else zq.zq_gemm_w4a8_dequant
     out, acc, _, _ = fn(dev(xq), dev(s_tok), dev(wq), dev(s_w), dev(bias), want_acc=True, workspace=ws)
     torch.cuda.synchronize()
@@ -80,7 +80,7 @@ def test_default_dispatch_w8a16(zq, orc, M, N, K, g):
     s_w = zq_inputs.random_scales(rng, g, 1e-4, 1e-2)
     bias = zq_inputs.bias(rng, N)
     nbytes = zq.gemm_w8a16_workspace_bytes(M, N, K)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = zq.new_workspace(nbytes)
     out = zq.zq_gemm_w8a16_dequant(dev(x), dev(codes), dev(s_w), dev(bias), workspace=ws)
     torch.cuda.synchronize()
     _check(orc, host(out), x, codes, s_w, bias, "random w8a16 %dx%dx%d" % (M, N, K))
