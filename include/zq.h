@@ -57,7 +57,8 @@ typedef enum {
     ZQ_ERR_SHAPE = 2,       /* a dimension is non-positive, not divisible as required, or too large */
     ZQ_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned */
     ZQ_ERR_UNSUPPORTED = 4, /* bits / dtype / flag value outside the supported set */
-    ZQ_ERR_HIP = 5          /* the HIP runtime reported an error at launch */
+    ZQ_ERR_HIP = 5,         /* the HIP runtime reported an error at launch */
+    ZQ_ERR_SCRATCH = 6      /* zq_gemm_i8_dequant_static: the shape needs more scratch than the static buffer holds */
 } zq_status;
 
 typedef void *zq_stream;
@@ -164,6 +165,26 @@ zq_status zq_gemm_i8_dequant(const int8_t *xq, const float *s_tok, const int8_t 
                              int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
                              int32_t *acc_out, int8_t *out_q, float *out_s_tok,
                              void *workspace, size_t workspace_bytes, zq_stream stream);
+
+/*
+ * zq_gemm_i8_dequant for callers that cannot allocate or be handed device memory beyond their
+ * tensors: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as zq_gemm_i8_dequant without the workspace pair: the workspace is a
+ * buffer inside the library's code object, ZQ_STATIC_SCRATCH_BYTES (16 MiB) per device, held by every
+ * device the library runs on until the process ends.  The call allocates and frees nothing.
+ *   - A shape whose schedule would use more workspace than that (zq_gemm_workspace_bytes, or
+ *     zq_gemm_quant_workspace_bytes when out_q is given) is refused with ZQ_ERR_SCRATCH and nothing
+ *     is launched; zq_gemm_i8_dequant with a caller's workspace takes such shapes.
+ *   - All calls of this entry point on one device share that device's buffer, and the buffer keeps
+ *     what the last call left (the kernels leave the control words, counters and slots ready for the
+ *     next call; partial sums are overwritten before they are read).  Calls must therefore be
+ *     ordered, on one stream or by events: two of them running at once on one device race.
+ * Other errors as zq_gemm_i8_dequant.
+ */
+#define ZQ_STATIC_SCRATCH_BYTES 16777216
+zq_status zq_gemm_i8_dequant_static(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w,
+                                    int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
+                                    int32_t *acc_out, int8_t *out_q, float *out_s_tok, zq_stream stream);
 
 /*
  * Same layer with INT4 weights (the W4/8 policy of Sec. 5 puts INT4 on the

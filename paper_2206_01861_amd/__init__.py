@@ -31,6 +31,8 @@ from .binding import (  # noqa: F401
     zq_gelu_quant_tokenwise,
     zq_gemm_gelu_quant_tokenwise,
     zq_gemm_i8_dequant,
+    zq_gemm_i8_dequant_static,
+    STATIC_SCRATCH_BYTES,
     zq_gemm_w4a8_dequant,
     zq_gemm_w8a16_dequant,
     zq_layernorm_quant_tokenwise,

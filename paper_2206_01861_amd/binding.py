@@ -20,7 +20,7 @@ SYMBOLS = [
     "zq_tune_set", "zq_tune_clear", "zq_tune_count", "zq_gemm_w8a16_dequant", "zq_gemm_w8a16_workspace_bytes",
     "zq_gemm_w8a16_stream_plan",
     "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
-    "zq_workspace_init", "zq_gemm_quant_workspace_bytes",
+    "zq_workspace_init", "zq_gemm_quant_workspace_bytes", "zq_gemm_i8_dequant_static",
 ]
 
 
@@ -61,6 +61,8 @@ def lib():
     L.zq_gemm_i8_dequant.argtypes = gemm_args
     L.zq_gemm_w4a8_dequant.restype = ci
     L.zq_gemm_w4a8_dequant.argtypes = gemm_args
+    L.zq_gemm_i8_dequant_static.restype = ci
+    L.zq_gemm_i8_dequant_static.argtypes = gemm_args[:13] + [vp]
     L.zq_gemm_gelu_quant_tokenwise.restype = ci
     L.zq_gemm_gelu_quant_tokenwise.argtypes = [vp, vp, vp, ci, vp, ci, vp, ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     L.zq_quantize_tokenwise.restype = ci
@@ -328,6 +330,41 @@ def zq_gemm_i8_dequant(xq, s_tok, wq, s_w, bias_fp16=None, want_acc=False, requa
     """-> (out fp16 [M,N], acc int32 | None, out_q int8 | None, out_s_tok fp32 | None)."""
     return _gemm(lib().zq_gemm_i8_dequant, torch.int8, xq, s_tok, wq, s_w, bias_fp16, want_acc, requant,
                  workspace, out, acc_out)
+
+
+STATIC_SCRATCH_BYTES = 16777216      # ZQ_STATIC_SCRATCH_BYTES of include/zq.h
+
+
+def zq_gemm_i8_dequant_static(xq, s_tok, wq, s_w, bias_fp16=None, requant=False, out=None, acc_out=None,
+                              out_q=None, out_s_tok=None):
+    """zq_gemm_i8_dequant on the library's static scratch buffer: the C call allocates nothing, and
+    neither does this wrapper when out (and acc_out, out_q, out_s_tok as wanted) are passed in.
+    -> (out, acc_out, out_q, out_s_tok)."""
+    _dev(xq, torch.int8, "xq")
+    _dev(s_tok, torch.float32, "s_tok")
+    _dev(wq, torch.int8, "wq")
+    _dev(s_w, torch.float32, "s_w")
+    if bias_fp16 is not None:
+        _dev(bias_fp16, torch.float16, "bias_fp16")
+    M, K = xq.shape
+    N = wq.shape[0]
+    _gemm_shapes(M, N, K, wq, 8, s_tok, bias_fp16)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _out_shape(_dev(out, torch.float16, "out"), M, N, "out")
+    if acc_out is not None:
+        _out_shape(_dev(acc_out, torch.int32, "acc_out"), M, N, "acc_out")
+    if requant and out_q is None:
+        out_q = torch.empty((M, N), dtype=torch.int8, device=xq.device)
+        out_s_tok = torch.empty(M, dtype=torch.float32, device=xq.device)
+    if out_q is not None:
+        _out_shape(_dev(out_q, torch.int8, "out_q"), M, N, "out_q")
+        if _dev(out_s_tok, torch.float32, "out_s_tok").numel() != M:
+            raise ValueError("out_s_tok must hold %d scales" % M)
+    _check(lib().zq_gemm_i8_dequant_static(_ptr(xq), _ptr(s_tok), _ptr(wq), _ptr(s_w), int(s_w.numel()),
+                                           _ptr(bias_fp16), M, N, K, _ptr(out), _ptr(acc_out), _ptr(out_q),
+                                           _ptr(out_s_tok), _stream()))
+    return out, acc_out, out_q, out_s_tok
 
 
 def zq_gemm_w4a8_dequant(xq, s_tok, wq4, s_w, bias_fp16=None, want_acc=False, requant=False, workspace=None,

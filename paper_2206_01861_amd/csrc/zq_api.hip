@@ -92,6 +92,7 @@ const char *zq_status_string(zq_status st) {
         case ZQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
         case ZQ_ERR_UNSUPPORTED: return "unsupported bits, dtype, flag or forced schedule";
         case ZQ_ERR_HIP: return "the HIP runtime reported an error";
+        case ZQ_ERR_SCRATCH: return "the shape needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -281,6 +282,52 @@ zq_status zq_gemm_w8a16_dequant(const void *x_fp16, const int8_t *wq, const floa
         e = zq::launch_gemm_a16_simple(a, st);
     }
     return e == hipSuccess ? ZQ_OK : ZQ_ERR_HIP;
+}
+
+}  // extern "C"
+
+// The workspace of zq_gemm_i8_dequant_static: one array per device, part of the loaded code
+// object (zero when the library is loaded, which is the state zq_workspace_init establishes).
+// In host code the name `scratch` only stands for the symbol; its address on a device comes from
+// hipGetSymbolAddress, asked once per device with that device current.
+namespace {
+constexpr size_t kScratchBytes = ZQ_STATIC_SCRATCH_BYTES;
+static_assert(kScratchBytes > zq::kWsFixedBytes && kScratchBytes % 256 == 0, "fixed part plus room for partial sums");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+std::atomic<void *> g_scratch_ptr[64];
+
+hipError_t scratch_on_current_device(void **out) {
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread gets the same answer
+    }
+    *out = p;
+    return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+zq_status zq_gemm_i8_dequant_static(const int8_t *xq, const float *s_tok, const int8_t *wq, const float *s_w,
+                                    int groups, const void *bias_fp16, int M, int N, int K, void *out_fp16,
+                                    int32_t *acc_out, int8_t *out_q, float *out_s_tok, zq_stream stream) {
+    // Shape errors first, as in the plain call; then the size of the scratch this shape would use.
+    if (M > 0 && N > 0 && K > 0) {
+        const size_t need = out_q != nullptr ? zq_gemm_quant_workspace_bytes(M, N, K, 8)
+                                             : zq_gemm_workspace_bytes(M, N, K, 8);
+        if (need > kScratchBytes) return ZQ_ERR_SCRATCH;
+    }
+    if (xq == nullptr || s_tok == nullptr || wq == nullptr || s_w == nullptr || out_fp16 == nullptr)
+        return ZQ_ERR_NULL;
+    void *ws = nullptr;
+    if (scratch_on_current_device(&ws) != hipSuccess) return ZQ_ERR_HIP;
+    return gemm_common(xq, s_tok, wq, s_w, groups, bias_fp16, M, N, K, out_fp16, acc_out, out_q, out_s_tok, ws,
+                       kScratchBytes, 8, 0, false, stream);
 }
 
 int zq_debug_force_gemm_variant(int variant) {
