@@ -9,8 +9,12 @@ captured once into a HIP graph and replayed (the paper replays a CUDA graph for
 both its INT8 and its FP16 runs, App. D); the FP16 comparator is captured the
 same way.  Prints ONE JSON line: whole-chain throughput in TOPS, the roofline
 of the dominant kernel (the tiled INT8 GeMM, launched twice per step), the
-same chain in FP16 through torch (hipBLASLt / rocBLAS), and the CPU oracle
-timed on the host cores.
+same chain in FP16 through torch (hipBLASLt / rocBLAS), the CPU oracle timed
+on the host cores, and a `rows` array with the GeMMs the roofline targets are
+stated on: the largest prefill shapes (against the INT8 matrix-core peak) and
+decode shapes whose weight buffers rotate through more than 512 MB (against
+the HBM peak), each the median of five repeats of at least fifty launches,
+with the oracle timed beside it.
 
 `python bench.py --table` instead times every linear of every workload shape
 (prefill: TOPS against the INT8 matrix-core peak; decode: GB/s against HBM,
@@ -34,9 +38,14 @@ import zq_inputs  # noqa: E402
 PEAK_INT8_TOPS = 5000.0    # MI355X dense INT8 matrix-core peak, TOP/s
 PEAK_HBM_GBS = 8000.0
 # HBM-side bytes one tiled-GeMM launch of the default workload moves, mean of the two launches of a
-# step: rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy
-# (profiles/c2_ffc_pair_hbm_traffic.txt; algorithmic bytes are 40 MiB and 28 MiB).
+# step: rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy.  A constant taken from the
+# profile named below, not measured in this run (algorithmic bytes are 40 MiB and 28 MiB).
 GEMM_TRAFFIC_BYTES = 56.4 * (1 << 20)
+GEMM_TRAFFIC_SOURCE = "profiles/c2_ffc_pair_hbm_traffic.txt"
+ROTATE_BYTES = 640 << 20   # decode rows: operands rotate through more than twice the 256 MB Infinity Cache
+# GeMMs reported next to the headline: (linear, tokens, bound)
+ROWS = [("c5_ffc1", 16384, "mfma"), ("c4_qkv", 4096, "mfma"), ("c5_ffc1", 64, "hbm"), ("c4_ffc1", 1, "hbm"),
+        ("c4_qkv", 1, "hbm"), ("c4_qkv", 16, "hbm")]
 
 
 def _events(n):
@@ -61,6 +70,67 @@ def graph_of(fn, reps):
         for i in range(reps):
             fn(i)
     return g
+
+
+class ClockSampler:
+    """Reads the shader clock from sysfs on a host thread while the GPU works; .mhz is the median of the
+    samples taken, or None where the file is not readable or the region was too short for a sample."""
+
+    def __init__(self):
+        self.samples, self._stop, self._thread, self.mhz = [], False, None, None
+
+    def _run(self):
+        while not self._stop:
+            v = sclk_mhz()
+            if v is None:
+                return
+            self.samples.append(v)
+            time.sleep(0.0005)
+
+    def __enter__(self):
+        import threading
+        self._thread = threading.Thread(target=self._run, daemon=True)
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._thread.join()
+        if self.samples:
+            self.mhz = float(np.median(self.samples))
+
+
+def time_graph_median(g, reps_per_replay, repeats=5, warm=1, clock=None):
+    """Median over `repeats` timed replays of a graph of `reps_per_replay` calls: ms per call.
+    clock: a dict that receives "sclk_mhz", the median shader clock sampled while the replays ran."""
+    for _ in range(warm):
+        g.replay()
+    torch.cuda.synchronize()
+    times = []
+    with ClockSampler() as cs:
+        for _ in range(repeats):
+            e0, e1 = _events(2)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) / reps_per_replay)
+    if clock is not None:
+        clock["sclk_mhz"] = cs.mhz
+    return float(np.median(times))
+
+
+def sclk_mhz():
+    """The shader clock the driver reports right now (sysfs), or None where it is not readable."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            for line in open(path):
+                if "*" in line:
+                    return float(line.split(":")[1].replace("*", "").strip().lower().replace("mhz", ""))
+        except (OSError, ValueError, IndexError):
+            continue
+    return None
 
 
 def time_graph(g, replays, reps_per_replay, warm=2):
@@ -189,16 +259,85 @@ def cpu_baseline(wl):
             "sample": "one step of the same chain, all %d tokens, %.2f s wall" % (wl.M, dt)}
 
 
+def rotated_frontends(zq, wl):
+    """LayerNorm+quant and GeLU+quant of the workload with inputs and outputs rotating through more
+    than 512 MB, so that neither the reads nor the writes are served by the Infinity Cache."""
+    M, H, F = wl.M, wl.H, wl.F
+    res = {}
+    n_ln = -(-ROTATE_BYTES // (3 * M * H))
+    xs = [torch.randn((M, H), device="cuda").half() for _ in range(n_ln)]
+    qs = [torch.empty((M, H), dtype=torch.int8, device="cuda") for _ in range(n_ln)]
+    reps = -(-50 // n_ln) * n_ln
+    g = graph_of(lambda i: zq.zq_layernorm_quant_tokenwise(xs[i % n_ln], wl.gamma, wl.beta, 1e-5,
+                                                           out=(qs[i % n_ln], wl.st)), reps)
+    us = time_graph_median(g, reps) * 1e3
+    res["layernorm_quant"] = {"us": us, "GBs": (3.0 * M * H + 4 * H + 4 * M) / (us * 1e-6) / 1e9, "sets": n_ln}
+    del xs, qs, g
+    n_g = -(-ROTATE_BYTES // (3 * M * F))
+    hs = [torch.randn((M, F), device="cuda").half() for _ in range(n_g)]
+    qs = [torch.empty((M, F), dtype=torch.int8, device="cuda") for _ in range(n_g)]
+    reps = -(-50 // n_g) * n_g
+    g = graph_of(lambda i: zq.zq_gelu_quant_tokenwise(hs[i % n_g], None, out=(qs[i % n_g], wl.st2)), reps)
+    us = time_graph_median(g, reps) * 1e3
+    res["gelu_quant"] = {"us": us, "GBs": (3.0 * M * F + 4 * M) / (us * 1e-6) / 1e9, "sets": n_g}
+    return res
+
+
+def c1_chain(zq):
+    """Workload c1 (one BERT-base linear at 128 tokens) as the chain LayerNorm+quant -> GeMM 768 -> 768:
+    HIP-graph replay against launching the two calls one by one (App. D: on small models the launches
+    cost more than the kernels)."""
+    rng = zq_inputs.rng_for(1, 0)
+    M, H, g = 128, 768, 48
+    x = _dev(zq_inputs.config_activations("c1", rng, M, H))
+    gamma_h, beta_h = zq_inputs.layernorm_params(rng, H)
+    gamma, beta = _dev(gamma_h), _dev(beta_h)
+    w, b = _dev(zq_inputs.weights(rng, H, H)), _dev(zq_inputs.bias(rng, H))
+    wq, sw = zq.zq_quantize_weight_groupwise(w, g, 8)
+    xq = torch.empty((M, H), dtype=torch.int8, device="cuda")
+    st = torch.empty(M, dtype=torch.float32, device="cuda")
+    out = torch.empty((M, H), dtype=torch.float16, device="cuda")
+
+    def chain(_=0):
+        zq.zq_layernorm_quant_tokenwise(x, gamma, beta, 1e-5, out=(xq, st))
+        zq.zq_gemm_i8_dequant(xq, st, wq, sw, b, out=out)
+
+    def fp16_chain(_=0):
+        y = torch.nn.functional.layer_norm(x, (H,), gamma, beta, 1e-5)
+        return torch.nn.functional.linear(y, w, b)
+
+    graph_us = time_graph_median(graph_of(chain, 50), 50) * 1e3
+    fp16_graph_us = time_graph_median(graph_of(fp16_chain, 50), 50) * 1e3
+    eager = []
+    for _ in range(5):
+        for _ in range(10):
+            chain()
+        torch.cuda.synchronize()
+        e0, e1 = _events(2)
+        e0.record()
+        for _ in range(50):
+            chain()
+        e1.record()
+        torch.cuda.synchronize()
+        eager.append(e0.elapsed_time(e1) * 1e3 / 50)
+    return {"graph_us": graph_us, "eager_us": float(np.median(eager)), "fp16_graph_us": fp16_graph_us,
+            "workload": "c1: LayerNorm+quant -> INT8 GeMM 768->768 at 128 tokens, 48 weight groups",
+            "timing": "median of 5 repeats of 50 chains; eager = the same calls issued one by one through the "
+                      "Python binding"}
+
+
 def run_default(args):
     import paper_2206_01861_amd as zq
     zq.lib()
     torch.cuda.set_device(0)
     wl = FFCPair(zq)
-    spg = 10                                    # steps per graph
-    replays = max(1, args.steps // spg)
-    steps = replays * spg
+    # exactly args.steps steps are timed: graphs of spg steps, spg the largest divisor of steps up to 10
+    steps = max(1, args.steps)
+    spg = max(d for d in range(1, 11) if steps % d == 0)
+    replays = steps // spg
     g = graph_of(wl.step, spg)
-    for _ in range(max(1, args.warmup // spg)):
+    warm_replays = -(-max(0, args.warmup) // spg)
+    for _ in range(warm_replays):
         g.replay()
     torch.cuda.synchronize()
     e0, e1 = _events(2)
@@ -209,38 +348,46 @@ def run_default(args):
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / steps
     tops = wl.ops / (ms_per_step * 1e-3) / 1e12
+    # the same chain as the median of five repeats of fifty steps, with the shader clock sampled meanwhile
+    clk = {}
+    step_median_ms = time_graph_median(graph_of(wl.step, 50), 50, repeats=5, clock=clk)
+    sclk = clk.get("sclk_mhz")
 
     # per-call durations: each call replayed back to back in a graph of its own, on the same stream
+    # (inputs and outputs of one call stay the same, so these are cache-warm figures)
     calls = {}
     for name, fn in (("layernorm_quant", wl.ln), ("gemm_ffc1", wl.gemm1), ("gelu_quant", wl.gelu),
                      ("gemm_ffc2", wl.gemm2)):
-        calls[name] = time_graph(graph_of(fn, 20), 10, 20) * 1e3          # us
+        calls[name] = time_graph_median(graph_of(fn, 50), 50, repeats=5, clock=clk) * 1e3          # us
+        if name.startswith("gemm"):
+            calls[name + "_sclk_mhz"] = clk.get("sclk_mhz")
     gemm_us = (calls["gemm_ffc1"] + calls["gemm_ffc2"]) / 2
     achieved = wl.gemm_ops / (gemm_us * 1e-6) / 1e12
 
     fused = None
-    if not args.no_fused:
-        fused_ms = time_graph(graph_of(wl.fused_step, spg), replays, spg)
-        fused = {"ms_per_step": fused_ms, "TOPS": wl.ops / (fused_ms * 1e-3) / 1e12,
-                 "gemm_ffc1_gelu_quant_us": time_graph(graph_of(wl.gemm1_gelu, 20), 10, 20) * 1e3,
-                 "gemm_ffc1_gelu_quant_with_fp16_output_us": time_graph(graph_of(wl.gemm1_gelu_keep, 20), 10, 20) * 1e3,
-                 "note": "zq_gemm_gelu_quant_tokenwise replaces GeMM 1 + GeLU+quant (three calls, the GeMM kernel "
-                         "quantizes its own output rows); not the headline value"}
-
     unfused = None
     if not args.no_fused:
-        unfused_ms = time_graph(graph_of(wl.unfused_step, spg), replays, spg)
-        unfused = {"ms_per_step": unfused_ms, "fusion_speedup": unfused_ms / ms_per_step,
+        fused_ms = time_graph_median(graph_of(wl.fused_step, 50), 50)
+        fused = {"ms_per_step": fused_ms, "TOPS": wl.ops / (fused_ms * 1e-3) / 1e12,
+                 "gemm_ffc1_gelu_quant_us": time_graph_median(graph_of(wl.gemm1_gelu, 50), 50) * 1e3,
+                 "gemm_ffc1_gelu_quant_with_fp16_output_us": time_graph_median(graph_of(wl.gemm1_gelu_keep, 50), 50) * 1e3,
+                 "note": "zq_gemm_gelu_quant_tokenwise replaces GeMM 1 + GeLU+quant (three calls, the GeMM kernel "
+                         "quantizes its own output rows); not the headline value"}
+        torch.cuda.synchronize()
+        expired = zq.quant_wait_expired(wl.ws)
+        if expired:
+            sys.exit("bench.py: %d waits of the in-kernel output quantization ran out; its figures are void" % expired)
+        unfused_ms = time_graph_median(graph_of(wl.unfused_step, 20), 20)
+        unfused = {"ms_per_step": unfused_ms, "fusion_speedup": unfused_ms / step_median_ms,
                    "note": "Fig. 2 (left): separate LayerNorm / GeLU (torch FP16), quantization, INT32 GeMM output and "
                            "dequantization kernels; eight launches instead of four"}
 
-    gf = graph_of(wl.fp16_step, spg)
-    fp16_ms = time_graph(gf, replays, spg)
-    fp16_gemm_us = time_graph(graph_of(lambda i: torch.nn.functional.linear(wl.x, wl.w1, wl.b1), 20), 10, 20) * 1e3
+    fp16_ms = time_graph_median(graph_of(wl.fp16_step, 50), 50)
+    fp16_gemm_us = time_graph_median(graph_of(lambda i: torch.nn.functional.linear(wl.x, wl.w1, wl.b1), 50), 50) * 1e3
 
     out = {
         "metric": "quantized-linear TOPS (W8A8, LayerNorm+quant -> GeMM -> GeLU+quant -> GeMM)",
-        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": warm_replays * spg,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "c2: BERT-large FFC pair 1024->4096->1024, 4096 tokens (batch 32 x seq 128), "
@@ -248,22 +395,50 @@ def run_default(args):
                    "tokens": wl.M, "hidden": wl.H, "ffn": wl.F, "groups": wl.g,
                    "launch": "HIP graph replay, %d steps per graph" % spg,
                    "offline_weight_quant_ms": wl.weight_quant_ms},
+        "ms_per_step_median": step_median_ms,
+        "timing": "value: exactly `steps` steps between two events; every other figure: median of 5 repeats of "
+                  ">= 50 launches (one graph replay per repeat)",
+        "sclk_mhz": sclk if sclk is not None else "unavailable",
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": achieved / PEAK_INT8_TOPS, "traffic": GEMM_TRAFFIC_BYTES,
+                     "traffic_source": GEMM_TRAFFIC_SOURCE + " (a constant from that profile, not measured in this run)",
                      "kernel": "gemm_tile_kernel (INT8 MFMA; one launch = one 4096-token GeMM of 2*4096*1024*4096 ops)",
                      "avg_launch_us": gemm_us},
         "calls_us": calls,
         "frontend_hbm": {
-            "layernorm_quant_GBs": (3.0 * wl.M * wl.H + 4 * wl.H + 4 * wl.M) / (calls["layernorm_quant"] * 1e-6) / 1e9,
-            "gelu_quant_GBs": (3.0 * wl.M * wl.F + 4 * wl.M) / (calls["gelu_quant"] * 1e-6) / 1e9,
+            "cache_warm": {
+                "layernorm_quant_GBs": (3.0 * wl.M * wl.H + 4 * wl.H + 4 * wl.M) / (calls["layernorm_quant"] * 1e-6) / 1e9,
+                "gelu_quant_GBs": (3.0 * wl.M * wl.F + 4 * wl.M) / (calls["gelu_quant"] * 1e-6) / 1e9,
+                "note": "the same 12 MB / 48 MB every launch: served in part by the 256 MB Infinity Cache"},
+            "rotated": rotated_frontends(zq, wl),
             "peak_GBs": PEAK_HBM_GBS},
         "fused_gelu_epilogue": fused,
         "unfused_pipeline": unfused,
-        "fp16": {"ms_per_step": fp16_ms, "speedup_chain": fp16_ms / ms_per_step,
+        "fp16": {"ms_per_step": fp16_ms, "speedup_chain": fp16_ms / step_median_ms,
                  "gemm_ffc1_us": fp16_gemm_us, "speedup_gemm_ffc1": fp16_gemm_us / calls["gemm_ffc1"]},
         "paper_context": "ZeroQuant reports whole-model W8A8 speed-ups on A100-40GB only "
                          "(BERT-large seq128: 2.62x at batch 1 to 5.01x at batch 128); no kernel-level figures",
     }
+    del g
+    torch.cuda.empty_cache()
+    out["c1_chain_us"] = c1_chain(zq)
+    if not args.no_rows:
+        rows = []
+        todo = ROWS
+        if args.rows:
+            todo = [(r.split(":")[0], int(r.split(":")[1]), "mfma" if int(r.split(":")[1]) > 128 else "hbm")
+                    for r in args.rows.split(",")]
+        for name, M, bound in todo:
+            r = time_gemm(zq, name, M, comparators=not args.no_fp16_rows, oracle=not args.no_cpu)
+            if bound == "mfma":
+                r["roofline"] = {"bound": "mfma", "achieved": r["TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                                 "frac": r["frac_int8_peak"]}
+            else:
+                r["roofline"] = {"bound": "hbm", "achieved": r["GBs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                 "frac": r["frac_hbm_peak"]}
+            rows.append(r)
+            torch.cuda.empty_cache()
+        out["rows"] = rows
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -295,13 +470,32 @@ def _codes(gen, rows, cols, cfg):
     return torch.round(x * (127.0 / a)).clamp_(-127, 127).to(torch.int8), (a[:, 0] / 127.0).float()
 
 
-def time_gemm(zq, name, M, reps_target=40):
+def oracle_gemm_baseline(xq_t, st_t, codes_h, sw_t, bias_t, M):
+    """The oracle's GeMM + epilogue on the host cores for one row of the table.  Prefill shapes (more
+    than 64 tokens) are timed on the first 64 rows and the time is scaled by M / 64."""
+    from oracle import zq_oracle as orc
+    rows = min(M, 64)
+    xq_h = xq_t[:rows].cpu().numpy()
+    st_h, sw_h, b_h = st_t[:rows].cpu().numpy(), sw_t.cpu().numpy(), bias_t.cpu().numpy()
+    t0 = time.perf_counter()
+    acc = orc.matmul_i32(xq_h, codes_h)
+    orc.dequant(acc, st_h, sw_h, b_h)
+    dt = (time.perf_counter() - t0) * (M / rows)
+    N, K = codes_h.shape
+    return {"value": 2.0 * M * N * K / dt / 1e12, "unit": "TOPS", "seconds": dt, "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": ("all %d rows" % M) if rows == M else ("first 64 rows, time scaled by %d/64" % M)}
+
+
+def time_gemm(zq, name, M, min_launches=50, repeats=5, comparators=True, oracle=False):
+    """One GeMM of the workload table: median of `repeats` timed graph replays of at least
+    `min_launches` launches each.  Up to 64 tokens the operands rotate through more than 512 MB."""
     K, N, g, bits = zq_inputs.LINEARS[name]
     cfg = name.split("_")[0]
     gen = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED % (2 ** 31) + M)
     wbytes = N * K * bits // 8
     per_set = wbytes + M * K + 2 * M * N
-    nset = int(max(1, min(32, -(-(640 << 20) // per_set)))) if M <= 64 else 1
+    nset = int(max(1, min(32, -(-ROTATE_BYTES // per_set)))) if M <= 64 else 1
     sets = []
     for _ in range(nset):
         xq, st = _codes(gen, M, K, cfg)
@@ -320,38 +514,61 @@ def time_gemm(zq, name, M, reps_target=40):
         xq, st, wq, sw, out = sets[i % nset]
         fn(xq, st, wq, sw, bias, workspace=ws, out=out)
 
-    reps = max(nset, reps_target // max(1, nset) * nset) if M <= 64 else 10
-    gq = graph_of(run, reps)
-    best = min(time_graph(gq, 3, reps, warm=1) for _ in range(3))          # ms per call
-    xf = torch.randn((M, K), device="cuda", dtype=torch.float16)
-    wfs = [torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.02
-           for _ in range(min(nset, max(1, (640 << 20) // (2 * N * K) + 1)) if M <= 64 else 1)]
-    gf = graph_of(lambda i: torch.nn.functional.linear(xf, wfs[i % len(wfs)], bias), reps)
-    fbest = min(time_graph(gf, 3, reps, warm=1) for _ in range(2))
-    del xf, wfs, gf, gq
-    # The vendor library's own INT8 GeMM (torch._int_mm -> hipBLASLt: INT32 output, no scales, no
-    # bias) on the prefill shapes, as a second comparator.
-    lib_int8 = None
-    if M > 128:
-        try:
-            xi = torch.randint(-127, 128, (M, K), device="cuda", dtype=torch.int8)
-            wi = torch.randint(-127, 128, (N, K), device="cuda", dtype=torch.int8).t()
-            torch._int_mm(xi, wi)
-            gi = graph_of(lambda i: torch._int_mm(xi, wi), 5)
-            lib_int8 = min(time_graph(gi, 2, 5, warm=1) for _ in range(2))
-            del xi, wi, gi
-        except Exception:                       # not every build routes _int_mm to a library kernel
-            lib_int8 = None
+    # launches per graph: a whole number of passes over the rotating sets; long launches need fewer
+    # for a stable figure (a 16384-token GeMM is milliseconds), the floor stays at min_launches / 5
     ops = 2.0 * M * N * K
+    reps = -(-min_launches // nset) * nset
+    if ops > 1e12:
+        reps = max(10, min_launches // 5)
+    gq = graph_of(run, reps)
+    clk = {}
+    best = time_graph_median(gq, reps, repeats=repeats, warm=1, clock=clk)          # ms per call
+    clock = clk.get("sclk_mhz")
+    del gq
+    fbest = lib_int8 = None
+    if comparators:
+        xf = torch.randn((M, K), device="cuda", dtype=torch.float16)
+        wfs = [torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.02
+               for _ in range(min(nset, max(1, ROTATE_BYTES // (2 * N * K) + 1)) if M <= 64 else 1)]
+        freps = reps if M <= 64 else 10
+        gf = graph_of(lambda i: torch.nn.functional.linear(xf, wfs[i % len(wfs)], bias), freps)
+        fbest = time_graph_median(gf, freps, repeats=3, warm=1)
+        del xf, wfs, gf
+        # The vendor library's own INT8 GeMM (torch._int_mm -> hipBLASLt: INT32 output, no scales, no
+        # bias) on the prefill shapes, as a second comparator.
+        if M > 128:
+            try:
+                xi = torch.randint(-127, 128, (M, K), device="cuda", dtype=torch.int8)
+                wi = torch.randint(-127, 128, (N, K), device="cuda", dtype=torch.int8).t()
+                torch._int_mm(xi, wi)
+                gi = graph_of(lambda i: torch._int_mm(xi, wi), 5)
+                lib_int8 = time_graph_median(gi, 5, repeats=3, warm=1)
+                del xi, wi, gi
+            except Exception:                       # not every build routes _int_mm to a library kernel
+                lib_int8 = None
     bytes_min = M * K + wbytes + 4 * M + 4 * g + 2 * N + 2 * M * N
     variant = zq.gemm_variant_name(zq.gemm_choose_variant(M, N, K, bits, nws))
-    return {"linear": name, "M": M, "N": N, "K": K, "w_bits": bits, "groups": g, "schedule": variant,
-            "us": best * 1e3, "TOPS": ops / (best * 1e-3) / 1e12, "GBs": bytes_min / (best * 1e-3) / 1e9,
-            "frac_int8_peak": ops / (best * 1e-3) / 1e12 / PEAK_INT8_TOPS,
-            "frac_hbm_peak": bytes_min / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "fp16_us": fbest * 1e3, "speedup_vs_fp16": fbest / best, "rotating_sets": nset,
-            "lib_int8_us": None if lib_int8 is None else lib_int8 * 1e3,
-            "speedup_vs_lib_int8": None if lib_int8 is None else lib_int8 / best}
+    row = {"linear": name, "M": M, "N": N, "K": K, "w_bits": bits, "groups": g, "schedule": variant,
+           "us": best * 1e3, "TOPS": ops / (best * 1e-3) / 1e12, "GBs": bytes_min / (best * 1e-3) / 1e9,
+           "frac_int8_peak": ops / (best * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+           "frac_hbm_peak": bytes_min / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
+           "ops": ops, "bytes_min": bytes_min,
+           "timing": "median of %d repeats of %d launches (one graph replay each)" % (repeats, reps),
+           "rotating_sets": nset, "rotating_bytes": nset * per_set,
+           "sclk_mhz": clock if clock is not None else "unavailable",
+           "fp16_us": None if fbest is None else fbest * 1e3,
+           "speedup_vs_fp16": None if fbest is None else fbest / best,
+           "lib_int8_us": None if lib_int8 is None else lib_int8 * 1e3,
+           "speedup_vs_lib_int8": None if lib_int8 is None else lib_int8 / best}
+    if oracle:
+        xq, st, wq, sw, _ = sets[0]
+        if bits == 8:
+            codes_h = wq.cpu().numpy()
+        else:
+            from oracle import zq_oracle as orc
+            codes_h = orc.unpack_int4(wq.cpu().numpy())
+        row["cpu_baseline"] = oracle_gemm_baseline(xq, st, codes_h, sw, bias, M)
+    return row
 
 
 def time_gemm_a16(zq, name, M, reps_target=40):
@@ -436,11 +653,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--rows", default="", help="comma-separated linear:tokens pairs replacing the default rows")
     ap.add_argument("--table", action="store_true", help="time every workload shape")
     ap.add_argument("--table-json", default=os.path.join(ROOT, "bench_table.json"),
                     help="with --table: where the rows are written as JSON")
     ap.add_argument("--only", default="", help="with --table: restrict to linears whose name starts with this")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-rows", action="store_true", help="skip the per-GeMM rows (large prefill and rotated decode shapes)")
+    ap.add_argument("--no-fp16-rows", action="store_true", help="rows without their FP16 comparator")
     ap.add_argument("--no-fused", action="store_true",
                     help="skip the extra three-call chain (keeps a profile of the default run to the headline kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
