@@ -186,9 +186,14 @@ __device__ __forceinline__ void apply_activation_n(float (&f)[N], int act) {
 // Workgroup barrier for kernels that keep asynchronous global->LDS loads in flight across it.
 // __syncthreads() carries a fence that drains every outstanding vector-memory operation
 // (s_waitcnt vmcnt(0)), which would serialise the load pipeline; here only LDS traffic is
-// drained, and the "memory" clobber keeps the compiler from moving accesses across the barrier.
+// drained.  The wait is emitted through the builtin so that the compiler's own wait-count
+// bookkeeping sees it: with the wait hidden inside an asm statement the compiler assumed the LDS
+// reads issued before the barrier could still be in flight after it, and made the matrix-core
+// instructions that follow the barrier (on operands read long before) wait for the first reads
+// issued after it.  The "memory" clobber keeps the compiler from moving accesses across the barrier.
 __device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0); vmcnt and expcnt untouched
+    asm volatile("s_barrier" ::: "memory");
 }
 
 }  // namespace zq

@@ -226,26 +226,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         kt0 = split * base + (split < rem ? split : rem);
         n_loc = base + (split < rem ? 1 : 0);
     }
-    auto issue_direct = [&](int kt, int slot) {
+    // `beyond`: the stage lies past this workgroup's range of K.  The loads are issued all the same,
+    // from an offset outside the buffer (the hardware writes zeros into the slot, which is free):
+    // with the same number of loads at every stage boundary the wait counts are constants and the
+    // boundary has no branch, so the compiler can interleave the fragment reads that follow it
+    // with the matrix-core instructions of the stage's last k step.
+    auto issue_direct = [&](int kt, int slot, bool beyond) {
         uint8_t *base = smem + slot * STAGE;
         const bool last = kt == nkt - 1;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             const int u = wave + NW * i;
-            const int vo = last ? voff_tail[i] : voff[i];
+            const int vo = beyond ? kNowhere : (last ? voff_tail[i] : voff[i]);
+            const int so = beyond ? 0 : kt * BK;
             if (i < XU / NW)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, vo, kt * BK, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, vo, so, 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_void *)(base + X_STAGE + (u - XU) * 1024), 16, vo,
-                                                         kt * BK, 0, 0);
+                                                         so, 0, 0);
         }
     };
     int32x4 w4_regs[W4_PASSES];
-    auto w4_fetch = [&](int kt) {
+    auto w4_fetch = [&](int kt, bool beyond) {
 #pragma unroll
         for (int p = 0; p < W4_PASSES; ++p) {
-            const bool inside = kt * (BK / 2) + ((int)threadIdx.x % TPR4) * 16 < wrow_bytes;
-            w4_regs[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, inside ? w4_voff[p] : kNowhere, kt * (BK / 2), 0);
+            const bool inside = !beyond && kt * (BK / 2) + ((int)threadIdx.x % TPR4) * 16 < wrow_bytes;
+            w4_regs[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, inside ? w4_voff[p] : kNowhere,
+                                                               beyond ? 0 : kt * (BK / 2), 0);
         }
     };
     auto w4_store = [&](int slot) {
@@ -337,12 +344,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     int32x4 a0[FN], b0[FM], a1[FN], b1[FM];
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
-        if (s < n_loc) {
-            issue_direct(kt0 + s, s);
-            if (STAGED_W) {
-                w4_fetch(kt0 + s);
-                w4_store(s);
-            }
+        issue_direct(kt0 + s, s, s >= n_loc);
+        if (STAGED_W && s < n_loc) {
+            w4_fetch(kt0 + s, false);
+            w4_store(s);
         }
     }
     // Scale prefetch (App. D reads both scale vectors before the product is complete): the
@@ -367,14 +372,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         }
         if (c < BM) row_scale[c] = st_v;
     }
-    if (!STAGED_W && n_loc >= NSTAGE)
+    if (!STAGED_W)
         wait_vmcnt<(NSTAGE - 1) * LPS>();      // stage 0 has landed; later stages may still be in flight
     else
         wait_vmcnt<0>();
     __syncthreads();
     read_frags(smem, 0, a0, b0);
 
-    for (int kt = 0; kt < n_loc; ++kt) {       // kt counts this workgroup's stages; kt0 + kt is the stage of K
+    // One stage of K.  The last stage of the workgroup is a copy of its own (LAST = 1) without the
+    // barrier, the refill and the read-ahead: were it a branch inside the loop, the paths with and
+    // without the barrier would meet again in front of the last matrix-core step, and the compiler,
+    // which tracks LDS reads in flight per path, would make that step wait for the reads issued after
+    // the barrier although its operands were read long before it.
+    auto stage = [&](int kt, auto last_c) __attribute__((always_inline)) {
+        constexpr bool LAST = decltype(last_c)::value;
         const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
         const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
 #pragma unroll
@@ -390,22 +401,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 if (STAGED_W && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < n_loc)
                     w4_store((kt + NSTAGE - 1) % NSTAGE);     // registers fetched at the previous stage boundary
             } else {
-                if (kt + 1 < n_loc) {
-                    if (!STAGED_W && kt + NSTAGE - 1 < n_loc)
+                if constexpr (!LAST) {
+                    if (!STAGED_W)
                         wait_vmcnt<(NSTAGE - 2) * LPS>();     // stage kt+1 has landed
                     else
                         wait_vmcnt<0>();
                     lds_barrier();
-                    if (kt + NSTAGE < n_loc) {
-                        issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE);
-                        if (STAGED_W) w4_fetch(kt0 + kt + NSTAGE);
-                    }
+                    issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE, kt + NSTAGE >= n_loc);
+                    if (STAGED_W) w4_fetch(kt0 + kt + NSTAGE, kt + NSTAGE >= n_loc);
                     read_frags(sn, 0, na, nb2);
                 }
                 mfma_step(ca, cb);
+                if constexpr (!LAST) interleave();     // the first fragments of the next stage arrive under these MFMAs
             }
         }
-    }
+    };
+    static_assert(KSTEPS % 2 == 0, "a stage starts on the first fragment set");
+    for (int kt = 0; kt < n_loc - 1; ++kt)     // kt counts this workgroup's stages; kt0 + kt is the stage of K
+        stage(kt, std::false_type{});
+    stage(n_loc - 1, std::true_type{});
 
     // ---- epilogue ---------------------------------------------------------
     // acc[fn][fm][v]: output column n = wn*WN + fn*32 + 8*(v/4) + 4*(lane/32) + v%4,
