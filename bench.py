@@ -259,6 +259,42 @@ def cpu_baseline(wl):
             "sample": "one step of the same chain, all %d tokens, %.2f s wall" % (wl.M, dt)}
 
 
+def measured_ceilings(zq):
+    """What the installed part sustains, next to the datasheet peaks (include/zq_probe.h): a read-only
+    stream over 1.25 GB, and the INT8 matrix cores alone on register operands of three kinds."""
+    res = {}
+    buf = torch.empty(1280 << 20, dtype=torch.uint8, device="cuda").random_(0, 256)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    g = graph_of(lambda i: zq.zq_probe_read_stream(buf, sink), 10)
+    ms = time_graph_median(g, 10)
+    res["hbm_read_stream_GBs"] = buf.numel() / (ms * 1e-3) / 1e9
+    del buf, g
+    torch.cuda.empty_cache()
+    blocks, iters = 512, 1500                      # two workgroups of four waves per compute unit
+    nbytes = blocks * 256 * 128
+    out = torch.empty(blocks * 256 * 16, dtype=torch.uint8, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(zq_inputs.BASE_SEED % (2 ** 31))
+    xq, _ = _codes(gen, nbytes // 2 // 4096, 4096, "c5")             # token-wise codes of N(0,1) rows
+    w = torch.randn((nbytes // 2 // 4096, 4096), generator=gen, device="cuda")
+    wq = torch.round(w * (127.0 / w.abs().amax())).to(torch.int8)      # one weight group
+    kinds = {"uniform_random_bytes": torch.randint(0, 256, (nbytes,), generator=gen, device="cuda", dtype=torch.uint8),
+             "workload_codes": torch.cat([xq.view(torch.uint8).flatten(), wq.view(torch.uint8).flatten()]),
+             "zero_operands": torch.zeros(nbytes, dtype=torch.uint8, device="cuda")}
+    for kind, ops_buf in kinds.items():
+        clk = {}
+        nops = [0]
+
+        def run(i, ops_buf=ops_buf):
+            nops[0] = zq.zq_probe_mfma_i8(ops_buf, blocks, iters, out)
+        g = graph_of(run, 5)
+        ms = time_graph_median(g, 5, clock=clk)
+        res["mfma_i8_TOPS_" + kind] = nops[0] / (ms * 1e-3) / 1e12
+        res["mfma_i8_sclk_mhz_" + kind] = clk.get("sclk_mhz")
+    res["note"] = ("matrix cores alone: 512 workgroups x 4 waves, 16 accumulators per wave, operands in registers; the "
+                   "clock, and with it the figure, follows the power the operand bytes make the multipliers draw")
+    return res
+
+
 def rotated_frontends(zq, wl):
     """LayerNorm+quant and GeLU+quant of the workload with inputs and outputs rotating through more
     than 512 MB, so that neither the reads nor the writes are served by the Infinity Cache."""
@@ -421,6 +457,9 @@ def run_default(args):
     }
     del g
     torch.cuda.empty_cache()
+    ceil = measured_ceilings(zq)
+    out["measured_ceilings"] = ceil
+    out["roofline"]["frac_of_measured_mfma_ceiling"] = achieved / ceil["mfma_i8_TOPS_workload_codes"]
     out["c1_chain_us"] = c1_chain(zq)
     if not args.no_rows:
         rows = []
@@ -432,10 +471,12 @@ def run_default(args):
             r = time_gemm(zq, name, M, comparators=not args.no_fp16_rows, oracle=not args.no_cpu)
             if bound == "mfma":
                 r["roofline"] = {"bound": "mfma", "achieved": r["TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                                 "frac": r["frac_int8_peak"]}
+                                 "frac": r["frac_int8_peak"],
+                                 "frac_of_measured_ceiling": r["TOPS"] / ceil["mfma_i8_TOPS_workload_codes"]}
             else:
                 r["roofline"] = {"bound": "hbm", "achieved": r["GBs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                 "frac": r["frac_hbm_peak"]}
+                                 "frac": r["frac_hbm_peak"],
+                                 "frac_of_measured_ceiling": r["GBs"] / ceil["hbm_read_stream_GBs"]}
             rows.append(r)
             torch.cuda.empty_cache()
         out["rows"] = rows

@@ -38,4 +38,6 @@ from .binding import (  # noqa: F401
     zq_layernorm_quant_tokenwise,
     zq_quantize_tokenwise,
     zq_quantize_weight_groupwise,
+    zq_probe_mfma_i8,
+    zq_probe_read_stream,
 )

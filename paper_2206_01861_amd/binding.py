@@ -22,6 +22,7 @@ SYMBOLS = [
     "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
     "zq_workspace_init", "zq_gemm_quant_workspace_bytes", "zq_gemm_i8_dequant_static",
 ]
+PROBE_SYMBOLS = ["zq_probe_read_stream", "zq_probe_mfma_i8"]      # include/zq_probe.h
 
 
 class ZQError(RuntimeError):
@@ -101,6 +102,10 @@ def lib():
     L.zq_gemm_w8a16_stream_plan.restype = ci
     L.zq_gemm_w8a16_stream_plan.argtypes = [ci, ci, ci, sz] + [ctypes.POINTER(ci)] * 3
     L.zq_gemm_stream_k_ranges.argtypes = [ci, ci, ci, ci, sz]
+    L.zq_probe_read_stream.restype = ci
+    L.zq_probe_read_stream.argtypes = [vp, sz, vp, vp]
+    L.zq_probe_mfma_i8.restype = ci
+    L.zq_probe_mfma_i8.argtypes = [vp, ci, ci, vp, vp]
     _lib = L
     return L
 
@@ -222,6 +227,24 @@ def gemm_w8a16_stream_plan(M, N, K, workspace_bytes=0):
 def gemm_stream_k_ranges(M, N, K, w_bits=8, workspace_bytes=0):
     """K ranges per strip inside a workgroup of the streaming schedules (1 or 2; 0: shape not taken)."""
     return lib().zq_gemm_stream_k_ranges(M, N, K, w_bits, workspace_bytes)
+
+
+def zq_probe_read_stream(buf, sink):
+    """Read every byte of `buf` (uint8 CUDA tensor, numel % 16 == 0) once; sink: 16-byte CUDA tensor."""
+    _dev(buf, torch.uint8, "buf")
+    _dev(sink, torch.uint8, "sink")
+    _check(lib().zq_probe_read_stream(_ptr(buf), buf.numel(), _ptr(sink), _stream()))
+
+
+def zq_probe_mfma_i8(operands, blocks, iters, sink):
+    """Matrix cores alone (include/zq_probe.h): operands uint8 [blocks*256*128], sink uint8 [blocks*256*16].
+    -> number of integer operations the launch performs."""
+    _dev(operands, torch.uint8, "operands")
+    _dev(sink, torch.uint8, "sink")
+    if operands.numel() < blocks * 256 * 128 or sink.numel() < blocks * 256 * 16:
+        raise ValueError("operands / sink too small for %d blocks" % blocks)
+    _check(lib().zq_probe_mfma_i8(_ptr(operands), blocks, iters, _ptr(sink), _stream()))
+    return blocks * 4 * iters * 16 * 65536
 
 
 def zq_quantize_weight_groupwise(w_fp16, groups, bits):

@@ -17,6 +17,7 @@ SOURCES = [
     "zq_gemm_skinny.hip",
     "zq_gemm_tile.hip",
     "zq_gemm_a16.hip",
+    "zq_probe.hip",
 ]
 
 # Packed FP32 instructions are kept off; everything else is plain -O3 for gfx950.

@@ -21,8 +21,8 @@ def test_workspace_constant_matches_the_header():
     assert FIXED == 256 + 8192 * 4 + (1 << 19) * 8
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "zq.h")).read()
+def _declared(header="zq.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(zq_[a-z0-9_]+)\s*\(", text)))
 
@@ -34,6 +34,20 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(L, n), n
     assert set(names) == set(binding.SYMBOLS)
+    probes = _declared("zq_probe.h")
+    assert set(probes) == set(binding.PROBE_SYMBOLS)
+    for n in probes:
+        assert hasattr(L, n), n
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["zq.h", "zq_probe.h"]
+
+
+def test_probe_validation():
+    rs, mf = zq.lib().zq_probe_read_stream, zq.lib().zq_probe_mfma_i8
+    assert rs(None, 1024, P, None) == E_NULL and rs(P, 1024, None, None) == E_NULL
+    assert rs(P, 1000, P, None) == E_SHAPE and rs(P, 0, P, None) == E_SHAPE
+    assert rs(P + 4, 1024, P, None) == E_ALIGN
+    assert mf(None, 8, 10, P, None) == E_NULL and mf(P, 0, 10, P, None) == E_SHAPE and mf(P, 8, 0, P, None) == E_SHAPE
+    assert mf(P, 8, 10, P + 8, None) == E_ALIGN
 
 
 def test_status_strings_and_version():
