@@ -398,14 +398,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                 read_frags(sb, ks + 1, na, nb2);
                 mfma_step(ca, cb);
                 interleave();
-                if (STAGED_W && ks == 0 && kt >= 1 && kt + NSTAGE - 1 < n_loc)
-                    w4_store((kt + NSTAGE - 1) % NSTAGE);     // registers fetched at the previous stage boundary
             } else {
                 if constexpr (!LAST) {
                     if (!STAGED_W)
                         wait_vmcnt<(NSTAGE - 2) * LPS>();     // stage kt+1 has landed
                     else
                         wait_vmcnt<0>();
+                    // Weights that pass through registers (INT4 nibbles, INT8 -> FP16): the registers fetched
+                    // at the previous boundary have had a whole stage to arrive and share the wait above;
+                    // their slot was freed at that boundary.  (Placed at the start of the stage, as before,
+                    // the store waited for loads issued one k step earlier, a full memory latency per stage.)
+                    if (STAGED_W && kt >= 1 && kt - 1 + NSTAGE < n_loc) w4_store((kt - 1) % NSTAGE);
                     lds_barrier();
                     issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE, kt + NSTAGE >= n_loc);
                     if (STAGED_W) w4_fetch(kt0 + kt + NSTAGE, kt + NSTAGE >= n_loc);
