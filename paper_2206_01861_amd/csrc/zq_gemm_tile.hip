@@ -478,69 +478,108 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     unsigned gen_raw = 0;                     // QOUT: generation of this launch, back before it is needed
     if constexpr (QOUT == 1)
         gen_raw = __hip_atomic_load(q_ctl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The column scales and biases of this wave's columns, read once where the registers allow it
+    // (they do not depend on the row).
+    constexpr bool HOIST = FN <= 2 && QOUT == 0;      // the in-kernel quantizer keeps the accumulators live longer
+    float4 sc_all[HOIST ? FN : 1][4], cb_all[HOIST ? FN : 1][4];
+    if constexpr (HOIST) {
 #pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-        rmax[fm] = 0.0f;
-        const float st = row_scale[wm * WM + fm * 32 + lr];
-#pragma unroll
-        for (int fn = 0; fn < FN; ++fn) {
+        for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int nl = fn * 32 + 8 * q + 4 * lc;
-                const float4 sc = *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
-                const float4 cb = *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
-                int32x4 v = {0, 0, 0, 0};
-                float fv[4];
-                if constexpr (XT == 1) {
+                sc_all[fn][q] = *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
+                cb_all[fn][q] = *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
+            }
+    }
+    // PLAIN = no activation and no accumulator tap, decided once for the whole epilogue: with the two
+    // (wave-uniform) tests inside the loops every group of four values was a basic block of its own
+    // and its LDS round trip could not overlap the arithmetic of its neighbours.
+    auto rows_pass = [&](auto plain_c) __attribute__((always_inline)) {
+        constexpr bool PLAIN = decltype(plain_c)::value;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) fv[e] = acc[fn][fm][4 * q + e];
-                } else {
-                    v = int32x4{acc[fn][fm][4 * q], acc[fn][fm][4 * q + 1], acc[fn][fm][4 * q + 2],
-                                acc[fn][fm][4 * q + 3]};
-                    if (WBITS == 4) {
+        for (int fm = 0; fm < FM; ++fm) {
+            rmax[fm] = 0.0f;
+            const float st = row_scale[wm * WM + fm * 32 + lr];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
+            for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = fn * 32 + 8 * q + 4 * lc;
+                    const float4 sc = HOIST ? sc_all[HOIST ? fn : 0][q]
+                                            : *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
+                    const float4 cb = HOIST ? cb_all[HOIST ? fn : 0][q]
+                                            : *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
+                    int32x4 v = {0, 0, 0, 0};
+                    float fv[4];
+                    if constexpr (XT == 1) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) fv[e] = acc[fn][fm][4 * q + e];
+                    } else {
+                        v = int32x4{acc[fn][fm][4 * q], acc[fn][fm][4 * q + 1], acc[fn][fm][4 * q + 2],
+                                    acc[fn][fm][4 * q + 3]};
+                        if (WBITS == 4) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] >>= 4;   // exact: every product carried the factor 16
+                        }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) fv[e] = (float)v[e];
                     }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) fv[e] = (float)v[e];
-                }
-                float f[4] = {fv[0] * (st * sc.x) + cb.x, fv[1] * (st * sc.y) + cb.y,
-                              fv[2] * (st * sc.z) + cb.z, fv[3] * (st * sc.w) + cb.w};
-                apply_activation_n<4>(f, act);    // act is wave-uniform
-                half4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (half_t)f[e];
-                if (QOUT == 0 || out != nullptr) *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
-                if (XT == 0 && acc_out != nullptr) {
-                    const int m = mw + fm * 32 + lr;
-                    if (m < M && nw + nl < N) *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
-                }
-                if constexpr (QOUT == 1) {
-                    // the accumulator registers now hold the output as rounded to FP16: the codes
-                    // below are those of the stored tensor
+                    // one rounded product of the two scales, then one fused multiply-add: written out so
+                    // that every instantiation of this epilogue rounds alike (left to the compiler, one
+                    // copy was contracted and another was not, one FP16 step apart on a few values)
+                    float f[4] = {__builtin_fmaf(fv[0], st * sc.x, cb.x), __builtin_fmaf(fv[1], st * sc.y, cb.y),
+                                  __builtin_fmaf(fv[2], st * sc.z, cb.z), __builtin_fmaf(fv[3], st * sc.w, cb.w)};
+                    if constexpr (!PLAIN) apply_activation_n<4>(f, act);    // act is wave-uniform
+                    half4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float g = (float)o[e];
-                        acc[fn][fm][4 * q + e] = __float_as_int(g);
-                        rmax[fm] = fmaxf(rmax[fm], fabsf(g));
+                        // the fp32 value is rounded to fp32 first and to FP16 second in every instantiation:
+                        // without this the compiler merges the multiply-add and the conversion of some
+                        // values into one mixed-precision instruction with a single rounding, and the
+                        // kernel that quantizes its output would not give the bits of the plain one
+                        asm("" : "+v"(f[e]));
+                        o[e] = (half_t)f[e];
+                    }
+                    if (QOUT == 0 || out != nullptr) *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
+                    if constexpr (!PLAIN && XT == 0) {
+                        if (acc_out != nullptr) {
+                            const int m = mw + fm * 32 + lr;
+                            if (m < M && nw + nl < N)
+                                *reinterpret_cast<int32x4 *>(acc_out + (size_t)m * N + nw + nl) = v;
+                        }
+                    }
+                    if constexpr (QOUT == 1) {
+                        // the accumulator registers now hold the output as rounded to FP16: the codes
+                        // below are those of the stored tensor
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float g = (float)o[e];
+                            acc[fn][fm][4 * q + e] = __float_as_int(g);
+                            rmax[fm] = fmaxf(rmax[fm], fabsf(g));
+                        }
                     }
                 }
             }
-        }
-        // The wave reads back its own 32 rows (LDS operations of one wave complete in order) and
-        // stores whole row segments.
-        if (QOUT == 0 || out != nullptr) {
+            // The wave reads back its own 32 rows (LDS operations of one wave complete in order) and
+            // stores whole row segments.
+            if (QOUT == 0 || out != nullptr) {
 #pragma unroll
-            for (int i = 0; i < 32 * LPR / 64; ++i) {
-                const int row = (i * 64 + lane) / LPR;
-                const int col = ((i * 64 + lane) % LPR) * 8;
-                const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
-                const int m = mw + fm * 32 + row;
-                const int n = nw + col;
-                if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+                for (int i = 0; i < 32 * LPR / 64; ++i) {
+                    const int row = (i * 64 + lane) / LPR;
+                    const int col = ((i * 64 + lane) % LPR) * 8;
+                    const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
+                    const int m = mw + fm * 32 + row;
+                    const int n = nw + col;
+                    if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+                }
             }
         }
-    }
+    };
+    if (QOUT == 0 && act == 0 && acc_out == nullptr)
+        rows_pass(std::true_type{});
+    else
+        rows_pass(std::false_type{});
 
     if constexpr (QOUT == 1) {
         // ---- token-wise quantization of the output rows from registers (App. A.2) ----
@@ -724,7 +763,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const int32x4 *__res
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float cb = (bias != nullptr) ? (float)bias[n + e] : 0.0f;
-            f[e] = fv[e] * (st * sc) + cb;
+            f[e] = __builtin_fmaf(fv[e], st * sc, cb);
         }
         apply_activation_n<4>(f, act);
         half4 o;
