@@ -75,9 +75,9 @@ __device__ __forceinline__ void unpack8_nat(uint32_t p, uint32_t &d0, uint32_t &
 constexpr unsigned kQuantSpinLimit = 1u << 20;        // polls of ~1 us: about a second, far beyond any launch
 constexpr unsigned kPoisonBits = 0x7fc00000u;         // a NaN; as an integer it is above the bits of every finite |g|
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int KT = 1>
 struct TileCfg {
-    static constexpr int kWaves = WAVES_M * WAVES_N;
+    static constexpr int kWaves = WAVES_M * WAVES_N * KT;
     static constexpr int kThreads = 64 * kWaves;
     static constexpr int kStage = (BM + BN) * BK;
     static constexpr int kWN = BN / WAVES_N;
@@ -86,7 +86,9 @@ struct TileCfg {
     static constexpr int kMain = NSTAGE * kStage > kEpi ? NSTAGE * kStage : kEpi;
     static constexpr int kLds = kMain + (2 * BN + BM) * 4;    // + column scale, column bias, row scale
     static constexpr int kLdsQ = kLds + (WAVES_N + 1) * BM * 4;   // + per-wave row maxima, row 1/scale
+    static constexpr int kXchg = (kEpi + 15) / 16 * 16;       // K teams: where the accumulator exchange starts
     static_assert(BM * BN <= kMain, "the INT8 code tile reuses the stage ring");
+    static_assert(KT == 1 || kXchg + BM * BN * 4 / 2 * KT <= NSTAGE * kStage, "the accumulator exchange reuses the stage ring");
 };
 
 }  // namespace
@@ -95,16 +97,22 @@ struct TileCfg {
 // KSPLIT = 1: the launch holds k_splits workgroups per tile, each multiplies its own range of K stages
 // and writes the raw accumulators of its tile to partial[split][M][N] (INT32, or fp32 bits with
 // XT = 1); a second kernel adds the splits and applies the epilogue (splitk_finish_kernel below).
+//
+// KT = 2: two teams of WAVES_M x WAVES_N waves share the tile and every stage in LDS; team t multiplies
+// k steps t*KSTEPS/2 .. of each stage, so a wave owns a tile twice as large as it would with all waves
+// side by side (a third fewer fragment reads per matrix-core instruction, and twice as many
+// instructions between a fragment read and its use).  After the last stage the teams exchange half of
+// their accumulators through LDS and each finishes half of the rows.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0,
-          int KSPLIT = 0>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 1 : 2) void gemm_tile_kernel(
+          int KSPLIT = 0, int KT = 1>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * KT >= 8) ? 1 : 2) void gemm_tile_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_tok, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int gs, const half_t *__restrict__ bias, int M, int N, int K,
     half_t *__restrict__ out, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int act,
     int8_t *__restrict__ q_out, float *__restrict__ q_scale_out, int k_splits, int32_t *__restrict__ partial,
     unsigned long long *__restrict__ q_slots, unsigned *__restrict__ q_ctl) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
-    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int NW = Cfg::kWaves;
     constexpr int NT = Cfg::kThreads;
@@ -113,6 +121,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
     constexpr int KSTEPS = BK / 32;
+    constexpr int KS_T = KSTEPS / KT;                // k steps of a stage that one team multiplies
+    static_assert(KT == 1 || KT == 2, "one or two K teams");
+    static_assert(KT == 1 || (QOUT == 0 && KSPLIT == 0), "K teams go with the plain epilogue");
+    static_assert(KT == 1 || FM % KT == 0, "each team finishes a whole number of 32-row blocks");
     constexpr int CPR = BK / 16;                     // 16-byte chunks per row
     constexpr int RPU = 64 / CPR;                    // rows per 1 KB load unit
     constexpr int XU = BM / RPU;                     // load units in the activation tile
@@ -294,7 +306,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[fn][fm][e] = 0;
 
-    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int team = (KT == 1) ? 0 : wave / (WAVES_M * WAVES_N);
+    const int wt = (KT == 1) ? wave : wave % (WAVES_M * WAVES_N);
+    const int wm = wt % WAVES_M, wn = wt / WAVES_M;
+    const int ks0 = team * KS_T;             // first k step of a stage that this wave multiplies
     const int lr = lane % 32;                // fragment row supplied by this lane
     const int lc = lane / 32;                // which 16-byte half of the 32-byte k step
     const int sw = swz<BK>(lr);              // wave and fragment offsets are multiples of 32 rows
@@ -304,7 +319,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // Fragment loads and matrix-core steps of one 32-byte k step, in the order
     // the MFMAs consume them: a[0], every bx, then the remaining a.
     auto read_frags = [&](const uint8_t *sb, int ks, int32x4(&a)[FN], int32x4(&bx)[FM]) {
-        const int p = ((ks * 2 + lc) ^ sw) * 16;
+        const int p = (((ks + ks0) * 2 + lc) ^ sw) * 16;
         a[0] = *reinterpret_cast<const int32x4 *>(sb + w_off + p);
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
@@ -389,12 +404,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
         const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
+        for (int ks = 0; ks < KS_T; ++ks) {
             int32x4(&ca)[FN] = (ks & 1) ? a1 : a0;
             int32x4(&cb)[FM] = (ks & 1) ? b1 : b0;
             int32x4(&na)[FN] = (ks & 1) ? a0 : a1;
             int32x4(&nb2)[FM] = (ks & 1) ? b0 : b1;
-            if (ks + 1 < KSTEPS) {
+            if (ks + 1 < KS_T) {
                 read_frags(sb, ks + 1, na, nb2);
                 mfma_step(ca, cb);
                 interleave();
@@ -419,7 +434,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
             }
         }
     };
-    static_assert(KSTEPS % 2 == 0, "a stage starts on the first fragment set");
+    static_assert(KS_T % 2 == 0, "a stage starts on the first fragment set");
     for (int kt = 0; kt < n_loc - 1; ++kt)     // kt counts this workgroup's stages; kt0 + kt is the stage of K
         stage(kt, std::false_type{});
     stage(n_loc - 1, std::true_type{});
@@ -468,6 +483,63 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
         return;
     }
     __syncthreads();                          // all reads of the last stage are done; LDS is reused below
+    if constexpr (KT == 2) {
+        // The two teams hold partial products of the same tile.  Each wave hands the half of its 32-row
+        // blocks that its partner wave (same place in the other team) will finish to LDS, one 16-byte piece
+        // per lane and group of four registers, and adds the partner's pieces for the half it keeps.
+        // Integer sums do not depend on the order; the fp32 ones are one addition of the same two
+        // numbers on either side.
+        constexpr int HALF = FM / 2;
+        int32x4 *xb = reinterpret_cast<int32x4 *>(smem + Cfg::kXchg);
+        constexpr int PER_WAVE = HALF * FN * 4 * 64;          // 16-byte pieces per wave
+        auto hand_over = [&](auto lo_c) __attribute__((always_inline)) {
+            constexpr int LO = decltype(lo_c)::value;         // first block handed over
+#pragma unroll
+            for (int fm = 0; fm < HALF; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        int32x4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if constexpr (XT == 1)
+                                v[e] = __float_as_int(acc[fn][LO + fm][4 * q + e]);
+                            else
+                                v[e] = acc[fn][LO + fm][4 * q + e];
+                        }
+                        xb[wave * PER_WAVE + ((fm * FN + fn) * 4 + q) * 64 + lane] = v;
+                    }
+        };
+        auto take_over = [&](auto lo_c) __attribute__((always_inline)) {
+            constexpr int LO = decltype(lo_c)::value;         // first block kept
+            const int partner = (wave + WAVES_M * WAVES_N) % (2 * WAVES_M * WAVES_N);
+#pragma unroll
+            for (int fm = 0; fm < HALF; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int32x4 v = xb[partner * PER_WAVE + ((fm * FN + fn) * 4 + q) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if constexpr (XT == 1)
+                                acc[fn][LO + fm][4 * q + e] += __int_as_float(v[e]);
+                            else
+                                acc[fn][LO + fm][4 * q + e] += v[e];
+                        }
+                    }
+        };
+        if (team == 0)
+            hand_over(std::integral_constant<int, HALF>{});   // team 0 keeps blocks 0 .. HALF-1
+        else
+            hand_over(std::integral_constant<int, 0>{});
+        __syncthreads();
+        if (team == 0)
+            take_over(std::integral_constant<int, 0>{});
+        else
+            take_over(std::integral_constant<int, HALF>{});
+    }
     constexpr int OROW = Cfg::kEpiRow;
     uint8_t *ot = smem + wave * (32 * OROW);  // wave-private: 32 rows of this wave's columns
     const int mw = m0 + wm * WM;              // first token row of this wave
@@ -495,10 +567,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
     // PLAIN = no activation and no accumulator tap, decided once for the whole epilogue: with the two
     // (wave-uniform) tests inside the loops every group of four values was a basic block of its own
     // and its LDS round trip could not overlap the arithmetic of its neighbours.
-    auto rows_pass = [&](auto plain_c) __attribute__((always_inline)) {
+    auto rows_pass = [&](auto plain_c, auto lo_c, auto hi_c) __attribute__((always_inline)) {
         constexpr bool PLAIN = decltype(plain_c)::value;
+        constexpr int FM_LO = decltype(lo_c)::value, FM_HI = decltype(hi_c)::value;   // the 32-row blocks this wave finishes
 #pragma unroll
-        for (int fm = 0; fm < FM; ++fm) {
+        for (int fm = FM_LO; fm < FM_HI; ++fm) {
             rmax[fm] = 0.0f;
             const float st = row_scale[wm * WM + fm * 32 + lr];
 #pragma unroll
@@ -571,15 +644,37 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
                     const int32x4 v = *reinterpret_cast<const int32x4 *>(ot + row * OROW + col * 2);
                     const int m = mw + fm * 32 + row;
                     const int n = nw + col;
-                    if (m < M && n < N) *reinterpret_cast<int32x4 *>(out + (size_t)m * N + n) = v;
+                    // Streaming (non-temporal) stores: nothing in this kernel reads the output again, and lines
+                    // that do not linger in the L2 need no write-back when the kernel ends (4096x4096x1024:
+                    // 25.3 -> 23.2 us alone, 23.5 -> 23.0 us inside the feed-forward chain).
+                    if (m < M && n < N)
+                        __builtin_nontemporal_store(v, reinterpret_cast<int32x4 *>(out + (size_t)m * N + n));
                 }
             }
         }
     };
-    if (QOUT == 0 && act == 0 && acc_out == nullptr)
-        rows_pass(std::true_type{});
-    else
-        rows_pass(std::false_type{});
+    const bool plain = QOUT == 0 && act == 0 && acc_out == nullptr;
+    using I0 = std::integral_constant<int, 0>;
+    using IH = std::integral_constant<int, FM / 2>;
+    using IF = std::integral_constant<int, FM>;
+    if constexpr (KT == 1) {
+        if (plain)
+            rows_pass(std::true_type{}, I0{}, IF{});
+        else
+            rows_pass(std::false_type{}, I0{}, IF{});
+    } else {
+        if (team == 0) {
+            if (plain)
+                rows_pass(std::true_type{}, I0{}, IH{});
+            else
+                rows_pass(std::false_type{}, I0{}, IH{});
+        } else {
+            if (plain)
+                rows_pass(std::true_type{}, IH{}, IF{});
+            else
+                rows_pass(std::false_type{}, IH{}, IF{});
+        }
+    }
 
     if constexpr (QOUT == 1) {
         // ---- token-wise quantization of the output rows from registers (App. A.2) ----
@@ -700,20 +795,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 
 #endif
 }
 
+
 namespace {
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0,
-          int KSPLIT = 0>
+          int KSPLIT = 0, int KT = 1>
 hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st, int k_splits = 1) {
-    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE>;
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT>;
     constexpr size_t lds = QOUT ? Cfg::kLdsQ : Cfg::kLds;
     static std::atomic<uint64_t> configured{0};
     const void *kernel = reinterpret_cast<const void *>(
-        &gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT>);
+        &gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT, KT>);
     if (hipError_t e = ensure_dynamic_lds(kernel, lds, configured); e != hipSuccess) return e;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     if (KSPLIT == 0 && k_splits != 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT>),
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, WBITS, XT, QOUT, KSPLIT, KT>),
                        dim3(tiles_m * tiles_n * k_splits), dim3(Cfg::kThreads), lds, st, a.xq, a.s_tok,
                        reinterpret_cast<const uint8_t *>(a.wq), a.s_w, a.N / a.groups,
                        reinterpret_cast<const half_t *>(a.bias), a.M, a.N, a.K, reinterpret_cast<half_t *>(a.out),
@@ -813,7 +909,7 @@ int quant_tile_edge(int M, int N) {
 
 // block: 256 = 256x256 tile, eight waves; 256192 = 256x192 tile, eight waves (4 x 2, wave tile 64 x 96);
 //        192 = 256x128 tile, four waves, two workgroups per CU;
-//        128 = 128x128 tile, eight waves on a deep ring of 128-byte stages (two waves per SIMD).
+//        128 = 128x128 tile, eight waves on a deep ring of 128-byte stages (two waves per SIMD); INT8 weights: two K teams.
 hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     if (block == 256) {
         if (a.w_bits == 8) return launch_tile_t<256, 256, 2, 4, 128, 2, 8>(a, st);
@@ -827,7 +923,10 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
         if (a.w_bits == 8) return launch_tile_t<256, 128, 2, 2, 64, 3, 8>(a, st);
         return launch_tile_t<256, 128, 2, 2, 64, 3, 4>(a, st);
     }
-    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 4, 128, 4, 8>(a, st);
+    // INT8 weights: two K teams of 2 x 2 waves (wave tile 64 x 64); measured 5-8 % ahead of eight waves side by
+    // side on 4096x1024x4096 and 2048x2048x8192, level on 2048x2048x2048.  INT4 weights measured 2-3 % slower with
+    // teams (the nibble unpack already fills the stage boundary) and keep the 2 x 4 layout.
+    if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 128, 4, 8, 0, 0, 0, 2>(a, st);
     return launch_tile_t<128, 128, 2, 4, 128, 4, 4>(a, st);
 }
 
