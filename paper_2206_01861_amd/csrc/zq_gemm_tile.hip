@@ -553,14 +553,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // The column scales and biases of this wave's columns, read once where the registers allow it
     // (they do not depend on the row).
     constexpr bool HOIST = FN <= 2 && QOUT == 0;      // the in-kernel quantizer keeps the accumulators live longer
-    float4 sc_all[HOIST ? FN : 1][4], cb_all[HOIST ? FN : 1][4];
+    // The four consecutive columns of a lane's register group lie in one weight group (a group is a
+    // multiple of 16 columns and the four start at a multiple of 4), so one scale serves all four.
+    float sc_all[HOIST ? FN : 1][4];
+    float4 cb_all[HOIST ? FN : 1][4];
     if constexpr (HOIST) {
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int nl = fn * 32 + 8 * q + 4 * lc;
-                sc_all[fn][q] = *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
+                sc_all[fn][q] = col_scale[wn * WN + nl];
                 cb_all[fn][q] = *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
             }
     }
@@ -579,8 +582,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int nl = fn * 32 + 8 * q + 4 * lc;
-                    const float4 sc = HOIST ? sc_all[HOIST ? fn : 0][q]
-                                            : *reinterpret_cast<const float4 *>(col_scale + wn * WN + nl);
+                    const float sc = HOIST ? sc_all[HOIST ? fn : 0][q] : col_scale[wn * WN + nl];
                     const float4 cb = HOIST ? cb_all[HOIST ? fn : 0][q]
                                             : *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
                     int32x4 v = {0, 0, 0, 0};
@@ -601,8 +603,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                     // one rounded product of the two scales, then one fused multiply-add: written out so
                     // that every instantiation of this epilogue rounds alike (left to the compiler, one
                     // copy was contracted and another was not, one FP16 step apart on a few values)
-                    float f[4] = {__builtin_fmaf(fv[0], st * sc.x, cb.x), __builtin_fmaf(fv[1], st * sc.y, cb.y),
-                                  __builtin_fmaf(fv[2], st * sc.z, cb.z), __builtin_fmaf(fv[3], st * sc.w, cb.w)};
+                    const float ss = st * sc;
+                    float f[4] = {__builtin_fmaf(fv[0], ss, cb.x), __builtin_fmaf(fv[1], ss, cb.y),
+                                  __builtin_fmaf(fv[2], ss, cb.z), __builtin_fmaf(fv[3], ss, cb.w)};
                     if constexpr (!PLAIN) apply_activation_n<4>(f, act);    // act is wave-uniform
                     half4 o;
 #pragma unroll
