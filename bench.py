@@ -290,8 +290,27 @@ def measured_ceilings(zq):
         ms = time_graph_median(g, 5, clock=clk)
         res["mfma_i8_TOPS_" + kind] = nops[0] / (ms * 1e-3) / 1e12
         res["mfma_i8_sclk_mhz_" + kind] = clk.get("sclk_mhz")
+    # the same matrix-core stream with the operand traffic of the 256x256 tile (LDS fragment reads and
+    # global -> LDS stages, no barriers, prologue or epilogue): the ceiling of that tile design on this part
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out2 = torch.empty(cus * 512 * 16, dtype=torch.uint8, device="cuda")
+    for kind in ("uniform_random_bytes", "workload_codes"):
+        nops = [0]
+
+        src2 = kinds[kind]
+        if kind == "workload_codes":                # the 2 MiB window the probe reads: half activation codes, half weight codes
+            src2 = torch.cat([xq.view(torch.uint8).flatten()[:1 << 20], wq.view(torch.uint8).flatten()[:1 << 20]])
+
+        def run2(i, src=src2):
+            nops[0] = zq.zq_probe_mfma_i8_tile_traffic(src, cus, 1500, out2)
+        g = graph_of(run2, 5)
+        ms = time_graph_median(g, 5)
+        res["mfma_i8_TOPS_with_tile_traffic_" + kind] = nops[0] / (ms * 1e-3) / 1e12
     res["note"] = ("matrix cores alone: 512 workgroups x 4 waves, 16 accumulators per wave, operands in registers; the "
-                   "clock, and with it the figure, follows the power the operand bytes make the multipliers draw")
+                   "clock, and with it the figure, follows the power the operand bytes make the multipliers draw. "
+                   "with_tile_traffic: one workgroup of eight waves per compute unit, every wave the 128x64 wave tile of "
+                   "the 256x256 schedule with its LDS fragment reads and its global->LDS stage loads, without barriers, "
+                   "prologue or epilogue")
     return res
 
 
@@ -460,6 +479,7 @@ def run_default(args):
     ceil = measured_ceilings(zq)
     out["measured_ceilings"] = ceil
     out["roofline"]["frac_of_measured_mfma_ceiling"] = achieved / ceil["mfma_i8_TOPS_workload_codes"]
+    out["roofline"]["frac_of_tile_traffic_ceiling"] = achieved / ceil["mfma_i8_TOPS_with_tile_traffic_workload_codes"]
     out["c1_chain_us"] = c1_chain(zq)
     if not args.no_rows:
         rows = []
@@ -472,7 +492,9 @@ def run_default(args):
             if bound == "mfma":
                 r["roofline"] = {"bound": "mfma", "achieved": r["TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                                  "frac": r["frac_int8_peak"],
-                                 "frac_of_measured_ceiling": r["TOPS"] / ceil["mfma_i8_TOPS_workload_codes"]}
+                                 "frac_of_measured_ceiling": r["TOPS"] / ceil["mfma_i8_TOPS_workload_codes"],
+                                 "frac_of_tile_traffic_ceiling":
+                                     r["TOPS"] / ceil["mfma_i8_TOPS_with_tile_traffic_workload_codes"]}
             else:
                 r["roofline"] = {"bound": "hbm", "achieved": r["GBs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                  "frac": r["frac_hbm_peak"],

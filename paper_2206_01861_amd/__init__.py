@@ -39,5 +39,6 @@ from .binding import (  # noqa: F401
     zq_quantize_tokenwise,
     zq_quantize_weight_groupwise,
     zq_probe_mfma_i8,
+    zq_probe_mfma_i8_tile_traffic,
     zq_probe_read_stream,
 )

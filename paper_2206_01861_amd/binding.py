@@ -22,7 +22,7 @@ SYMBOLS = [
     "zq_gemm_quantizes_in_kernel", "zq_debug_set_in_kernel_quant", "zq_quant_wait_expired",
     "zq_workspace_init", "zq_gemm_quant_workspace_bytes", "zq_gemm_i8_dequant_static",
 ]
-PROBE_SYMBOLS = ["zq_probe_read_stream", "zq_probe_mfma_i8"]      # include/zq_probe.h
+PROBE_SYMBOLS = ["zq_probe_read_stream", "zq_probe_mfma_i8", "zq_probe_mfma_i8_tile_traffic"]      # include/zq_probe.h
 
 
 class ZQError(RuntimeError):
@@ -106,6 +106,8 @@ def lib():
     L.zq_probe_read_stream.argtypes = [vp, sz, vp, vp]
     L.zq_probe_mfma_i8.restype = ci
     L.zq_probe_mfma_i8.argtypes = [vp, ci, ci, vp, vp]
+    L.zq_probe_mfma_i8_tile_traffic.restype = ci
+    L.zq_probe_mfma_i8_tile_traffic.argtypes = [vp, sz, ci, ci, vp, vp]
     _lib = L
     return L
 
@@ -245,6 +247,17 @@ def zq_probe_mfma_i8(operands, blocks, iters, sink):
         raise ValueError("operands / sink too small for %d blocks" % blocks)
     _check(lib().zq_probe_mfma_i8(_ptr(operands), blocks, iters, _ptr(sink), _stream()))
     return blocks * 4 * iters * 16 * 65536
+
+
+def zq_probe_mfma_i8_tile_traffic(source, blocks, iters, sink):
+    """Matrix cores with the operand traffic of the 256x256 tile (include/zq_probe.h): source uint8, at least
+    2 MiB; sink uint8 [blocks*512*16].  -> number of integer operations the launch performs."""
+    _dev(source, torch.uint8, "source")
+    _dev(sink, torch.uint8, "sink")
+    if source.numel() < (2 << 20) or sink.numel() < blocks * 512 * 16:
+        raise ValueError("source / sink too small for %d blocks" % blocks)
+    _check(lib().zq_probe_mfma_i8_tile_traffic(_ptr(source), source.numel(), blocks, iters, _ptr(sink), _stream()))
+    return blocks * 8 * iters * 32 * 65536
 
 
 def zq_quantize_weight_groupwise(w_fp16, groups, bits):

@@ -48,6 +48,10 @@ def test_probe_validation():
     assert rs(P + 4, 1024, P, None) == E_ALIGN
     assert mf(None, 8, 10, P, None) == E_NULL and mf(P, 0, 10, P, None) == E_SHAPE and mf(P, 8, 0, P, None) == E_SHAPE
     assert mf(P, 8, 10, P + 8, None) == E_ALIGN
+    tt = zq.lib().zq_probe_mfma_i8_tile_traffic
+    assert tt(None, 2 << 20, 8, 10, P, None) == E_NULL and tt(P, 2 << 20, 8, 10, None, None) == E_NULL
+    assert tt(P, (2 << 20) - 16, 8, 10, P, None) == E_SHAPE and tt(P, 2 << 20, 0, 10, P, None) == E_SHAPE
+    assert tt(P, 2 << 20, 8, 0, P, None) == E_SHAPE and tt(P + 4, 2 << 20, 8, 10, P, None) == E_ALIGN
 
 
 def test_status_strings_and_version():
