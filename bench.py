@@ -496,9 +496,15 @@ def run_default(args):
                                  "frac_of_tile_traffic_ceiling":
                                      r["TOPS"] / ceil["mfma_i8_TOPS_with_tile_traffic_workload_codes"]}
             else:
+                floor_us = read_stream_floor_us(zq, r["bytes_min"])
                 r["roofline"] = {"bound": "hbm", "achieved": r["GBs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                  "frac": r["frac_hbm_peak"],
-                                 "frac_of_measured_ceiling": r["GBs"] / ceil["hbm_read_stream_GBs"]}
+                                 "frac_of_measured_ceiling": r["GBs"] / ceil["hbm_read_stream_GBs"],
+                                 "read_stream_same_bytes_us": floor_us,
+                                 "read_stream_same_bytes_note": "the read-only probe over the row's algorithmic bytes "
+                                 "per launch, buffers rotating through 1.25 GB: what one launch needs to pull these "
+                                 "bytes from HBM, without any arithmetic or output",
+                                 "time_over_read_stream": r["us"] / floor_us}
             rows.append(r)
             torch.cuda.empty_cache()
         out["rows"] = rows
@@ -548,6 +554,22 @@ def oracle_gemm_baseline(xq_t, st_t, codes_h, sw_t, bias_t, M):
     return {"value": 2.0 * M * N * K / dt / 1e12, "unit": "TOPS", "seconds": dt, "cores": orc.num_threads(),
             "kind": "oracle",
             "sample": ("all %d rows" % M) if rows == M else ("first 64 rows, time scaled by %d/64" % M)}
+
+
+def read_stream_floor_us(zq, nbytes, min_launches=50):
+    """What the read-only probe (include/zq_probe.h) takes for `nbytes` per launch, the launches walking
+    through a 1.25 GB buffer: the time a single launch needs just to pull that many bytes out of HBM,
+    launch and ramp included.  The decode rows are read against it."""
+    n = max(4096, int(nbytes) // 4096 * 4096)
+    big = torch.empty(1280 << 20, dtype=torch.uint8, device="cuda").random_(0, 256)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    nset = max(1, big.numel() // n)
+    reps = -(-min_launches // nset) * nset
+    g = graph_of(lambda i: zq.zq_probe_read_stream(big[(i % nset) * n:(i % nset) * n + n], sink), reps)
+    ms = time_graph_median(g, reps)
+    del g, big
+    torch.cuda.empty_cache()
+    return ms * 1e3
 
 
 def time_gemm(zq, name, M, min_launches=50, repeats=5, comparators=True, oracle=False):

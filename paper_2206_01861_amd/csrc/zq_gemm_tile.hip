@@ -75,11 +75,11 @@ __device__ __forceinline__ void unpack8_nat(uint32_t p, uint32_t &d0, uint32_t &
 constexpr unsigned kQuantSpinLimit = 1u << 20;        // polls of ~1 us: about a second, far beyond any launch
 constexpr unsigned kPoisonBits = 0x7fc00000u;         // a NaN; as an integer it is above the bits of every finite |g|
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int KT = 1>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int KT = 1, int XT = 0>
 struct TileCfg {
     static constexpr int kWaves = WAVES_M * WAVES_N * KT;
     static constexpr int kThreads = 64 * kWaves;
-    static constexpr int kStage = (BM + BN) * BK;
+    static constexpr int kStage = BM * BK + BN * (XT == 1 ? BK / 2 : BK);   // XT = 1: INT8 weight rows next to FP16 activation rows
     static constexpr int kWN = BN / WAVES_N;
     static constexpr int kEpiRow = kWN * 2 + 16;              // padded FP16 row of the wave-private buffer
     static constexpr int kEpi = kWaves * 32 * kEpiRow;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     int8_t *__restrict__ q_out, float *__restrict__ q_scale_out, int k_splits, int32_t *__restrict__ partial,
     unsigned long long *__restrict__ q_slots, unsigned *__restrict__ q_ctl) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
-    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT>;
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT, XT>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int NW = Cfg::kWaves;
     constexpr int NT = Cfg::kThreads;
@@ -128,19 +128,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     constexpr int CPR = BK / 16;                     // 16-byte chunks per row
     constexpr int RPU = 64 / CPR;                    // rows per 1 KB load unit
     constexpr int XU = BM / RPU;                     // load units in the activation tile
-    constexpr int WU = BN / RPU;
-    // XT = 1: FP16 activations (W8A16).  A stage row is still BK bytes, now BK/2 values of K; the INT8
-    // weights take the register path of the INT4 weights (16 source bytes -> two 16-byte chunks) with
-    // an exact INT8 -> FP16 conversion instead of the nibble unpack, and the MFMA is the FP16 one.
-    constexpr bool STAGED_W = (WBITS == 4) || (XT == 1);
-    constexpr int XB = (XT == 1) ? 2 : 1;            // bytes per activation value
+    // XT != 0: FP16 activations (W8A16); the MFMA is the FP16 one and an activation row of a stage is still
+    // BK bytes, now BK/2 values of K.
+    // XT = 1: the weight rows stay INT8 in LDS (BK/2 bytes per stage, direct loads like the activations) and
+    // become FP16 in registers after the fragment read: one 16-byte read holds the weights of two k
+    // steps, converted exactly by cvt8_i8_f16.  So that a lane's sixteen weights meet the right
+    // activations, the k steps of a stage take the activation chunks in a permuted order (see
+    // read_x_a16): a sum over K does not depend on the order of K.
+    // XT = 2: the weights take the register path of the INT4 weights (16 source bytes -> two 16-byte
+    // chunks) with the same conversion instead of the nibble unpack, and sit in LDS as FP16.
+    constexpr bool A16 = XT != 0;
+    constexpr int BKW = (XT == 1) ? BK / 2 : BK;     // bytes of a weight row per stage
+    constexpr int CPRW = BKW / 16;
+    constexpr int RPUW = 64 / CPRW;
+    constexpr int WU = BN / RPUW;
+    constexpr bool STAGED_W = (WBITS == 4) || (XT == 2);   // weights that pass through registers on their way into LDS
+    constexpr int XB = A16 ? 2 : 1;                  // bytes per activation value
     static_assert(XT == 0 || WBITS == 8, "FP16 activations go with INT8 weights");
+    static_assert(XT != 1 || (BK == 128 && KT == 1), "the FP16-activation loop is written for four k steps per stage");
     static_assert(QOUT == 0 || XT == 0, "the output quantization is built for the INT8 product");
     static_assert(KSPLIT == 0 || QOUT == 0, "a K split leaves the epilogue to the second kernel");
-    constexpr int DIRECT_UNITS = STAGED_W ? XU : (XU + WU);
-    static_assert(XU % NW == 0 && WU % NW == 0, "load units must split evenly over the waves");
-    using AccT = typename std::conditional<XT == 1, float32x16, int32x16>::type;
-    constexpr int LPS = DIRECT_UNITS / NW;           // direct loads per wave per stage
+    static_assert(XU % NW == 0, "activation load units must split evenly over the waves");
+    constexpr int LX = XU / NW;                      // activation loads per wave per stage
+    // weight loads per wave per stage; where the units do not split evenly some waves load a unit a
+    // second time (the same bytes to the same place), so that every wave issues the same number of loads
+    constexpr int LWD = STAGED_W ? 0 : (WU + NW - 1) / NW;
+    using AccT = typename std::conditional<A16, float32x16, int32x16>::type;
+    constexpr int LPS = LX + LWD;                    // direct loads per wave per stage
     constexpr int TPR4 = BK / 32;                    // INT4: threads per row (16 packed bytes each)
     constexpr int W4_ROWS = NT / TPR4;               // rows per pass
     constexpr int W4_PASSES = (BN + W4_ROWS - 1) / W4_ROWS;
@@ -191,19 +205,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // rest weight rows.  Rows past the matrix edge are clamped to the last row:
     // loaded, multiplied, never stored.
     int voff[LPS];
+    // weight unit of this wave's load i (wave-uniform; a subtraction, not a remainder, which would go
+    // through the vector unit and make the LDS address of the load look divergent)
+    static_assert(LWD * NW <= 2 * WU || STAGED_W, "a unit is loaded at most twice");
+    auto w_unit = [&](int i) {
+        const int u = wave + NW * (i - LX);
+        return __builtin_amdgcn_readfirstlane(u >= WU ? u - WU : u);
+    };
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
-        const int u = wave + NW * i;
-        if (i < XU / NW) {
-            const int row = u * RPU + lane / CPR;
+        if (i < LX) {
+            const int row = (wave + NW * i) * RPU + lane / CPR;
             int grow = m0 + row;
             if (grow > M - 1) grow = M - 1;
             voff[i] = grow * xrow_bytes + (((lane % CPR) ^ swz<BK>(row)) * 16);
         } else {
-            const int row = (u - XU) * RPU + lane / CPR;
+            const int row = w_unit(i) * RPUW + lane / CPRW;
             int grow = n0 + row;
             if (grow > N - 1) grow = N - 1;
-            voff[i] = grow * wrow_bytes + (((lane % CPR) ^ swz<BK>(row)) * 16);
+            voff[i] = grow * wrow_bytes + (((lane % CPRW) ^ swz<BKW>(row)) * 16);
         }
     }
     // K need not be a multiple of the stage depth: in the last stage the chunks past the end of a
@@ -211,13 +231,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // plain offset would run into the next row); zero operands add nothing to the product.
     constexpr int kNowhere = 0x7ffffff0;
     const int tail_bytes = xrow_bytes % BK;           // valid bytes of the last stage row, 0 = full
+    const int tail_bytes_w = tail_bytes / XB;         // the same values of K in an INT8 weight row
     int voff_tail[LPS];
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
-        const int u = wave + NW * i;
-        const int row = ((i < XU / NW) ? u : (u - XU)) * RPU + lane / CPR;
-        const int chunk = (lane % CPR) ^ swz<BK>(row);
-        voff_tail[i] = (tail_bytes == 0 || chunk * 16 < tail_bytes) ? voff[i] : kNowhere;
+        if (i < LX) {
+            const int row = (wave + NW * i) * RPU + lane / CPR;
+            const int chunk = (lane % CPR) ^ swz<BK>(row);
+            voff_tail[i] = (tail_bytes == 0 || chunk * 16 < tail_bytes) ? voff[i] : kNowhere;
+        } else {
+            const int row = w_unit(i) * RPUW + lane / CPRW;
+            const int chunk = (lane % CPRW) ^ swz<BKW>(row);
+            voff_tail[i] = (tail_bytes == 0 || chunk * 16 < tail_bytes_w) ? voff[i] : kNowhere;
+        }
     }
     // INT4 weights: thread -> (row = pass*W4_ROWS + tid/TPR4, 16 packed bytes = 32 codes = chunks 2q, 2q+1)
     int w4_voff[W4_PASSES];
@@ -246,16 +272,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     auto issue_direct = [&](int kt, int slot, bool beyond) {
         uint8_t *base = smem + slot * STAGE;
         const bool last = kt == nkt - 1;
+        // the stage's byte offset inside a row is the same for every lane: said explicitly, so that it is
+        // never taken for a per-lane value (which would wrap each load in a loop over its distinct values)
+        const int so_x = __builtin_amdgcn_readfirstlane(beyond ? 0 : kt * BK);
+        const int so_w = __builtin_amdgcn_readfirstlane(beyond ? 0 : kt * BKW);
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
-            const int u = wave + NW * i;
             const int vo = beyond ? kNowhere : (last ? voff_tail[i] : voff[i]);
-            const int so = beyond ? 0 : kt * BK;
-            if (i < XU / NW)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + u * 1024), 16, vo, so, 0, 0);
+            if (i < LX)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void *)(base + (wave + NW * i) * 1024), 16, vo, so_x,
+                                                         0, 0);
             else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_void *)(base + X_STAGE + (u - XU) * 1024), 16, vo,
-                                                         so, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_void *)(base + X_STAGE + w_unit(i) * 1024), 16, vo,
+                                                         so_w, 0, 0);
         }
     };
     int32x4 w4_regs[W4_PASSES];
@@ -275,7 +304,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
             const int q = (int)threadIdx.x % TPR4;
             if (BN % W4_ROWS == 0 || row < BN) {   // the last pass may reach past the tile
                 uint32_t d[8];
-                if (XT == 1) {
+                if (XT == 2) {
                     const uint32x4_t lo = __builtin_bit_cast(
                         uint32x4_t, cvt8_i8_f16((uint32_t)w4_regs[p][0], (uint32_t)w4_regs[p][1]));
                     const uint32x4_t hi = __builtin_bit_cast(
@@ -314,7 +343,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     const int lc = lane / 32;                // which 16-byte half of the 32-byte k step
     const int sw = swz<BK>(lr);              // wave and fragment offsets are multiples of 32 rows
     const int x_off = (wm * WM + lr) * BK;
-    const int w_off = X_STAGE + (wn * WN + lr) * BK;
+    const int w_off = X_STAGE + (wn * WN + lr) * BKW;
 
     // Fragment loads and matrix-core steps of one 32-byte k step, in the order
     // the MFMAs consume them: a[0], every bx, then the remaining a.
@@ -327,16 +356,84 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         for (int fn = 1; fn < FN; ++fn) a[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BK + p);
     };
     auto mfma_step = [&](const int32x4(&a)[FN], const int32x4(&bx)[FM]) {
+        if constexpr (XT != 1) {
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    if constexpr (XT == 2)
+                        acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a[fn]),
+                                                                              __builtin_bit_cast(half8, bx[fm]),
+                                                                              acc[fn][fm], 0, 0, 0);
+                    else
+                        acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
+        }
+    };
+    // FP16 activations.  A stage holds 64 values of K: 128 bytes (eight chunks) of an activation row, 64 bytes
+    // (four chunks) of a weight row, four k steps of sixteen values.  Lane (row lr, half lc) reads weight
+    // chunk 2*pair + lc once per pair of k steps: its first eight codes feed the first step of the pair, its
+    // last eight the second.  The activations of the same values of K are chunk 4*pair + 2*lc + t for step
+    // t of the pair, so every step reads one 16-byte activation chunk per row as before.
+    const int sww = swz<BKW>(lr);
+    auto read_x_a16 = [&](const uint8_t *sb, int ks, int32x4(&bx)[FM]) {
+        const int p = (((ks / 2) * 4 + 2 * lc + (ks & 1)) ^ sw) * 16;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
+    };
+    int32x4 w_raw[FN];                       // the INT8 weights of the next pair of k steps
+    half8 w_f16[2][FN];                      // [step of the pair][fragment]: one set, rewritten once the
+                                             // second step's MFMAs have been issued (register budget)
+    auto read_w_a16 = [&](const uint8_t *sb, int pair) {
+        const int p = ((pair * 2 + lc) ^ sww) * 16;
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) w_raw[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BKW + p);
+    };
+    // first (T = 0) or last (T = 1) eight codes of w_raw -> the FP16 operands of that step of the pair
+    auto convert_w_a16 = [&](auto t_c) __attribute__((always_inline)) {
+        constexpr int T = decltype(t_c)::value;
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
+            w_f16[T][fn] = cvt8_i8_f16((uint32_t)w_raw[fn][2 * T], (uint32_t)w_raw[fn][2 * T + 1]);
+    };
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
+    // order of issue inside a step: one LDS read per MFMA while reads are left, then the conversion
+    // spread over the remaining MFMAs
+    auto pace_a16 = [&](auto reads_c) __attribute__((always_inline)) {
+        constexpr int READS = decltype(reads_c)::value;
+        constexpr int NM = FN * FM;
+        constexpr int VC = 10 * FN;                // VALU instructions of one conversion
+        if constexpr (READS < NM) {
+            constexpr int PER = (VC + NM - READS - 1) / (NM - READS);
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm)
-                if constexpr (XT == 1)
-                    acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a[fn]),
-                                                                          __builtin_bit_cast(half8, bx[fm]), acc[fn][fm], 0,
-                                                                          0, 0);
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
+                if (i < READS)
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // DS read
                 else
-                    acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);             // VALU
+            }
+        } else {                                   // small wave tiles: the reads outnumber the MFMAs
+            constexpr int PER = (READS + NM - 1) / NM;
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x002, VC, 0);
+        }
+    };
+    using RX = std::integral_constant<int, FM>;          // a step that reads activation fragments only
+    using RXW = std::integral_constant<int, FM + FN>;    // ... and the raw weights of the next pair
+    auto mfma_step_a16 = [&](const half8(&a)[FN], const int32x4(&bx)[FM]) {
+        if constexpr (XT == 1) {
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fn], __builtin_bit_cast(half8, bx[fm]),
+                                                                          acc[fn][fm], 0, 0, 0);
+        }
     };
     // one LDS read after every (FN*FM)/(FN+FM) MFMAs
     auto interleave = [&]() {
@@ -380,7 +477,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         const float sw_v = s_w[n / gs];
         // without a bias the load reads a valid dummy address: no branch around a load in flight
         const half_t b_v = *(bias != nullptr ? bias + n : reinterpret_cast<const half_t *>(s_w));
-        const float st_v = (XT == 1) ? 1.0f : s_tok[m];   // FP16 activations carry no token scale
+        const float st_v = A16 ? 1.0f : s_tok[m];         // FP16 activations carry no token scale
         if (c < BN) {
             col_scale[c] = sw_v;
             col_bias[c] = (bias != nullptr) ? (float)b_v : 0.0f;
@@ -392,7 +489,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     else
         wait_vmcnt<0>();
     __syncthreads();
-    read_frags(smem, 0, a0, b0);
+    if constexpr (XT == 1) {
+        read_x_a16(smem, 0, b0);
+        read_w_a16(smem, 0);
+        convert_w_a16(T0{});
+        convert_w_a16(T1{});
+    } else {
+        read_frags(smem, 0, a0, b0);
+    }
 
     // One stage of K.  The last stage of the workgroup is a copy of its own (LAST = 1) without the
     // barrier, the refill and the read-ahead: were it a branch inside the loop, the paths with and
@@ -403,6 +507,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         constexpr bool LAST = decltype(last_c)::value;
         const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
         const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
+        if constexpr (XT == 1) {
+            // k steps 0..3 = (pair 0, step 0), (pair 0, step 1), (pair 1, step 0), (pair 1, step 1).  The second
+            // step of a pair reads the raw weights of the next pair and converts their first half (whose
+            // registers the first step has finished with) under its own MFMAs; the first step of the next
+            // pair converts the second half under its MFMAs.  One set of converted operands is enough.
+            read_x_a16(sb, 1, b1);
+            mfma_step_a16(w_f16[0], b0);
+            convert_w_a16(T1{});
+            pace_a16(RX{});
+            read_x_a16(sb, 2, b0);
+            read_w_a16(sb, 1);
+            mfma_step_a16(w_f16[1], b1);
+            convert_w_a16(T0{});
+            pace_a16(RXW{});
+            read_x_a16(sb, 3, b1);
+            mfma_step_a16(w_f16[0], b0);
+            convert_w_a16(T1{});
+            pace_a16(RX{});
+            if constexpr (!LAST) {
+                wait_vmcnt<(NSTAGE - 2) * LPS>();         // stage kt+1 has landed
+                lds_barrier();
+                issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE, kt + NSTAGE >= n_loc);
+                read_x_a16(sn, 0, b0);
+                read_w_a16(sn, 0);
+            }
+            mfma_step_a16(w_f16[1], b1);
+            if constexpr (!LAST) {
+                convert_w_a16(T0{});
+                pace_a16(RXW{});
+            }
+            return;
+        }
 #pragma unroll
         for (int ks = 0; ks < KS_T; ++ks) {
             int32x4(&ca)[FN] = (ks & 1) ? a1 : a0;
@@ -462,7 +598,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                     int32x4 v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        if constexpr (XT == 1)
+                        if constexpr (A16)
                             v[e] = __float_as_int(acc[fn][fm][4 * q + e]);
                         else
                             v[e] = acc[fn][fm][4 * q + e];
@@ -503,7 +639,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                         int32x4 v;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            if constexpr (XT == 1)
+                            if constexpr (A16)
                                 v[e] = __float_as_int(acc[fn][LO + fm][4 * q + e]);
                             else
                                 v[e] = acc[fn][LO + fm][4 * q + e];
@@ -523,7 +659,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                         const int32x4 v = xb[partner * PER_WAVE + ((fm * FN + fn) * 4 + q) * 64 + lane];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            if constexpr (XT == 1)
+                            if constexpr (A16)
                                 acc[fn][LO + fm][4 * q + e] += __int_as_float(v[e]);
                             else
                                 acc[fn][LO + fm][4 * q + e] += v[e];
@@ -587,7 +723,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                                             : *reinterpret_cast<const float4 *>(col_bias + wn * WN + nl);
                     int32x4 v = {0, 0, 0, 0};
                     float fv[4];
-                    if constexpr (XT == 1) {
+                    if constexpr (A16) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) fv[e] = acc[fn][fm][4 * q + e];
                     } else {
@@ -804,7 +940,7 @@ namespace {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int WBITS, int XT = 0, int QOUT = 0,
           int KSPLIT = 0, int KT = 1>
 hipError_t launch_tile_t(const GemmArgs &a, hipStream_t st, int k_splits = 1) {
-    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT>;
+    using Cfg = TileCfg<BM, BN, WAVES_M, WAVES_N, BK, NSTAGE, KT, XT>;
     constexpr size_t lds = QOUT ? Cfg::kLdsQ : Cfg::kLds;
     static std::atomic<uint64_t> configured{0};
     const void *kernel = reinterpret_cast<const void *>(
@@ -1061,7 +1197,9 @@ hipError_t launch_gemm_a16_tile(const A16Args &a16, hipStream_t st) {
     const long c192 = rounds(rows256 * ((a.N + 191) / 192)) * 49152 * 115;
     const long c128 = rounds((long)((a.M + 127) / 128) * ((a.N + 127) / 128)) * 16384 * 185;
     if (c128 <= c256 && c128 <= c192) return launch_tile_t<128, 128, 2, 4, 128, 4, 8, 1>(a, st);
-    if (c192 < c256) return launch_tile_t<256, 192, 4, 2, 128, 2, 8, 1>(a, st);
+    // the 256x192 tile keeps its weights FP16 in LDS (XT = 2): with three weight fragments per wave the
+    // register-side conversion made the compiler copy the accumulators every stage
+    if (c192 < c256) return launch_tile_t<256, 192, 4, 2, 128, 2, 8, 2>(a, st);
     return launch_tile_t<256, 256, 2, 4, 128, 2, 8, 1>(a, st);
 }
 

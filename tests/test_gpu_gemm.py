@@ -227,7 +227,7 @@ def test_quantized_linear_end_to_end(zq, orc):
 # oracle plus the Freivalds identity on every accumulator, in the launch configuration the benchmark times
 # (default dispatch, a workspace of the size the library asks for).
 FULL = [(name, M) for name in zq_inputs.LINEARS for M in zq_inputs.TOKENS[name.split("_")[0]]]
-assert len(FULL) == 37
+assert len(FULL) == 39
 
 
 @pytest.mark.parametrize("name,M", FULL)

@@ -39,6 +39,7 @@ LINEARS = {
     "c5_qkv": (6144, 18432, 192, 8),
     "c5_ffc1": (6144, 24576, 192, 8),
     "c5_ffc2": (24576, 6144, 192, 8),
+    "c5_out": (6144, 6144, 192, 8),       # the attention output projection of the same layer (the configuration lists none)
 }
 
 # token counts each configuration is exercised at
