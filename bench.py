@@ -40,7 +40,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes one tiled-GeMM launch of the default workload moves, mean of the two launches of a
 # step: rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy.  A constant taken from the
 # profile named below, not measured in this run (algorithmic bytes are 40 MiB and 28 MiB).
-GEMM_TRAFFIC_BYTES = 56.4 * (1 << 20)
+GEMM_TRAFFIC_BYTES = 56.3 * (1 << 20)
 GEMM_TRAFFIC_SOURCE = "profiles/c2_ffc_pair_hbm_traffic.txt"
 ROTATE_BYTES = 640 << 20   # decode rows: operands rotate through more than twice the 256 MB Infinity Cache
 # GeMMs reported next to the headline: (linear, tokens, bound)

@@ -31,6 +31,16 @@
 // over its own range of K stages, and write raw accumulators to a workspace;
 // splitk_finish_kernel adds them and applies the epilogue.
 //
+// KT = 2 (128 x 128 tile, INT8 weights) splits the eight waves into two teams
+// that share every stage and take half of its k steps each, so that a wave
+// owns 64 x 64 instead of 64 x 32; the teams add their accumulators through
+// LDS after the last stage.
+//
+// XT != 0 is the product of FP16 activations with INT8 weights (Sec. 5, the
+// W8A16 setting): FP16 matrix-core instructions, fp32 accumulators, the
+// weights made FP16 exactly either after the fragment read (XT = 1: INT8 in
+// LDS) or on their way into LDS (XT = 2).
+//
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
 // in that XCD's L2.
