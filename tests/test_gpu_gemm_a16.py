@@ -38,6 +38,7 @@ SHAPES = [
     # ... the tiled schedules (128x128 and 256x256 tiles, ragged edges) ...
     (300, 400, 384, 25), (515, 1024, 1024, 64), (129, 272, 2048, 17), (2500, 4112, 512, 257),
     (515, 1024, 400, 64), (300, 1040, 1008, 65),       # K not a multiple of the stage depth
+    (2300, 7152, 336, 3),                              # 256x256 tiles (one round of 252), ragged in M, N and K
     # ... and with a K split
     (32, 2048, 8192, 128), (7, 528, 24576, 11), (64, 4112, 16384, 1), (1, 2048, 8192, 128),
     # above 128 tokens with few tiles and a long K: the tiled schedule splits K (fp32 partials, second kernel)
