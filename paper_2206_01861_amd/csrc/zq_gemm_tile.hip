@@ -277,8 +277,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // `beyond`: the stage lies past this workgroup's range of K.  The loads are issued all the same,
     // from an offset outside the buffer (the hardware writes zeros into the slot, which is free):
     // with the same number of loads at every stage boundary the wait counts are constants and the
-    // boundary has no branch, so the compiler can interleave the fragment reads that follow it
-    // with the matrix-core instructions of the stage's last k step.
+    // boundary needs no branch, so the compiler can interleave the fragment reads that follow it
+    // with the matrix-core instructions of the stage's last k step.  (Whether it then selects the
+    // offsets or still branches around the loads varies between instantiations; forcing the
+    // selection with masks it cannot see through measured level on INT8 and 2-3 % slower on INT4
+    // weights and FP16 activations, so the expressions are left as they read best.)
     auto issue_direct = [&](int kt, int slot, bool beyond) {
         uint8_t *base = smem + slot * STAGE;
         const bool last = kt == nkt - 1;
