@@ -36,10 +36,12 @@
 // owns 64 x 64 instead of 64 x 32; the teams add their accumulators through
 // LDS after the last stage.
 //
-// XT != 0 is the product of FP16 activations with INT8 weights (Sec. 5, the
+// XT = 1, 2 is the product of FP16 activations with INT8 weights (Sec. 5, the
 // W8A16 setting): FP16 matrix-core instructions, fp32 accumulators, the
 // weights made FP16 exactly either after the fragment read (XT = 1: INT8 in
-// LDS) or on their way into LDS (XT = 2).
+// LDS) or on their way into LDS (XT = 2).  XT = 3 is XT = 1's operand path
+// for INT4 weights under INT8 activations: the nibbles stay packed in LDS
+// (direct loads, half the bytes) and are unpacked after the fragment read.
 //
 // Workgroup ids are remapped so that the workgroups an XCD receives
 // (round-robin by id) cover a compact block of tiles and share operand panels
@@ -89,7 +91,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NSTAGE, int KT =
 struct TileCfg {
     static constexpr int kWaves = WAVES_M * WAVES_N * KT;
     static constexpr int kThreads = 64 * kWaves;
-    static constexpr int kStage = BM * BK + BN * (XT == 1 ? BK / 2 : BK);   // XT = 1: INT8 weight rows next to FP16 activation rows
+    static constexpr int kStage = BM * BK + BN * ((XT == 1 || XT == 3) ? BK / 2 : BK);   // XT = 1, 3: weight rows half as long as activation rows
     static constexpr int kWN = BN / WAVES_N;
     static constexpr int kEpiRow = kWN * 2 + 16;              // padded FP16 row of the wave-private buffer
     static constexpr int kEpi = kWaves * 32 * kEpiRow;
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     constexpr int CPR = BK / 16;                     // 16-byte chunks per row
     constexpr int RPU = 64 / CPR;                    // rows per 1 KB load unit
     constexpr int XU = BM / RPU;                     // load units in the activation tile
-    // XT != 0: FP16 activations (W8A16); the MFMA is the FP16 one and an activation row of a stage is still
+    // XT = 1, 2: FP16 activations (W8A16); the MFMA is the FP16 one and an activation row of a stage is still
     // BK bytes, now BK/2 values of K.
     // XT = 1: the weight rows stay INT8 in LDS (BK/2 bytes per stage, direct loads like the activations) and
     // become FP16 in registers after the fragment read: one 16-byte read holds the weights of two k
@@ -147,15 +149,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // read_x_a16): a sum over K does not depend on the order of K.
     // XT = 2: the weights take the register path of the INT4 weights (16 source bytes -> two 16-byte
     // chunks) with the same conversion instead of the nibble unpack, and sit in LDS as FP16.
-    constexpr bool A16 = XT != 0;
-    constexpr int BKW = (XT == 1) ? BK / 2 : BK;     // bytes of a weight row per stage
+    // XT = 3: INT8 activations, INT4 weights packed in LDS (again BK/2 bytes of a weight row per stage):
+    // XT = 1's loop with the nibble unpack as the conversion and the INT8 MFMA.
+    constexpr bool A16 = XT == 1 || XT == 2;
+    constexpr bool PAIRED = XT == 1 || XT == 3;      // weight rows half as long as activation rows, widened after the fragment read
+    constexpr int BKW = PAIRED ? BK / 2 : BK;        // bytes of a weight row per stage
     constexpr int CPRW = BKW / 16;
     constexpr int RPUW = 64 / CPRW;
     constexpr int WU = BN / RPUW;
-    constexpr bool STAGED_W = (WBITS == 4) || (XT == 2);   // weights that pass through registers on their way into LDS
+    constexpr bool STAGED_W = (WBITS == 4 && XT != 3) || (XT == 2);   // weights that pass through registers on their way into LDS
     constexpr int XB = A16 ? 2 : 1;                  // bytes per activation value
-    static_assert(XT == 0 || WBITS == 8, "FP16 activations go with INT8 weights");
-    static_assert(XT != 1 || (BK == 128 && KT == 1), "the FP16-activation loop is written for four k steps per stage");
+    static_assert(!A16 || WBITS == 8, "FP16 activations go with INT8 weights");
+    static_assert(XT != 3 || WBITS == 4, "packed weight rows in LDS are the INT4 ones");
+    static_assert(!PAIRED || (BK == 128 && KT == 1), "the paired loop is written for four k steps per stage");
     static_assert(QOUT == 0 || XT == 0, "the output quantization is built for the INT8 product");
     static_assert(KSPLIT == 0 || QOUT == 0, "a K split leaves the epilogue to the second kernel");
     static_assert(XU % NW == 0, "activation load units must split evenly over the waves");
@@ -241,7 +247,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // plain offset would run into the next row); zero operands add nothing to the product.
     constexpr int kNowhere = 0x7ffffff0;
     const int tail_bytes = xrow_bytes % BK;           // valid bytes of the last stage row, 0 = full
-    const int tail_bytes_w = tail_bytes / XB;         // the same values of K in an INT8 weight row
+    const int tail_bytes_w = tail_bytes / (PAIRED ? 2 : XB);   // the same values of K in a weight row
     int voff_tail[LPS];
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
@@ -369,7 +375,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         for (int fn = 1; fn < FN; ++fn) a[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BK + p);
     };
     auto mfma_step = [&](const int32x4(&a)[FN], const int32x4(&bx)[FM]) {
-        if constexpr (XT != 1) {
+        if constexpr (!PAIRED) {
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
@@ -382,7 +388,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                         acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
         }
     };
-    // FP16 activations.  A stage holds 64 values of K: 128 bytes (eight chunks) of an activation row, 64 bytes
+    // Weight rows half as long as activation rows (PAIRED), told for FP16 activations; with INT8 activations and
+    // INT4 weights a stage holds 128 values of K and every count of values below doubles.  A stage holds 64 values of K: 128 bytes (eight chunks) of an activation row, 64 bytes
     // (four chunks) of a weight row, four k steps of sixteen values.  Lane (row lr, half lc) reads weight
     // chunk 2*pair + lc once per pair of k steps: its first eight codes feed the first step of the pair, its
     // last eight the second.  The activations of the same values of K are chunk 4*pair + 2*lc + t for step
@@ -393,20 +400,29 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
     };
-    int32x4 w_raw[FN];                       // the INT8 weights of the next pair of k steps
-    half8 w_f16[2][FN];                      // [step of the pair][fragment]: one set, rewritten once the
+    int32x4 w_raw[FN];                       // the narrow weights of the next pair of k steps
+    using WOp = typename std::conditional<A16, half8, int32x4>::type;
+    WOp w_f16[2][FN];                        // [step of the pair][fragment]: one set, rewritten once the
                                              // second step's MFMAs have been issued (register budget)
     auto read_w_a16 = [&](const uint8_t *sb, int pair) {
         const int p = ((pair * 2 + lc) ^ sww) * 16;
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) w_raw[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BKW + p);
     };
-    // first (T = 0) or last (T = 1) eight codes of w_raw -> the FP16 operands of that step of the pair
+    // first (T = 0) or last (T = 1) eight bytes of w_raw -> the operands of that step of the pair (eight INT8
+    // codes to FP16, or sixteen nibbles to INT8 times 16, both exact)
     auto convert_w_a16 = [&](auto t_c) __attribute__((always_inline)) {
         constexpr int T = decltype(t_c)::value;
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
-            w_f16[T][fn] = cvt8_i8_f16((uint32_t)w_raw[fn][2 * T], (uint32_t)w_raw[fn][2 * T + 1]);
+            if constexpr (A16) {
+                w_f16[T][fn] = cvt8_i8_f16((uint32_t)w_raw[fn][2 * T], (uint32_t)w_raw[fn][2 * T + 1]);
+            } else {
+                uint32_t d0, d1, d2, d3;
+                unpack8_nat((uint32_t)w_raw[fn][2 * T], d0, d1);
+                unpack8_nat((uint32_t)w_raw[fn][2 * T + 1], d2, d3);
+                w_f16[T][fn] = int32x4{(int)d0, (int)d1, (int)d2, (int)d3};
+            }
     };
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
@@ -438,14 +454,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     };
     using RX = std::integral_constant<int, FM>;          // a step that reads activation fragments only
     using RXW = std::integral_constant<int, FM + FN>;    // ... and the raw weights of the next pair
-    auto mfma_step_a16 = [&](const half8(&a)[FN], const int32x4(&bx)[FM]) {
-        if constexpr (XT == 1) {
+    auto mfma_step_a16 = [&](const WOp(&a)[FN], const int32x4(&bx)[FM]) {
+        if constexpr (PAIRED) {
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
-                    acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fn], __builtin_bit_cast(half8, bx[fm]),
-                                                                          acc[fn][fm], 0, 0, 0);
+                    if constexpr (A16)
+                        acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fn], __builtin_bit_cast(half8, bx[fm]),
+                                                                              acc[fn][fm], 0, 0, 0);
+                    else
+                        acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fn], bx[fm], acc[fn][fm], 0, 0, 0);
         }
     };
     // one LDS read after every (FN*FM)/(FN+FM) MFMAs
@@ -502,7 +521,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     else
         wait_vmcnt<0>();
     __syncthreads();
-    if constexpr (XT == 1) {
+    if constexpr (PAIRED) {
         read_x_a16(smem, 0, b0);
         read_w_a16(smem, 0);
         convert_w_a16(T0{});
@@ -520,7 +539,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         constexpr bool LAST = decltype(last_c)::value;
         const uint8_t *sb = smem + (kt % NSTAGE) * STAGE;
         const uint8_t *sn = smem + ((kt + 1) % NSTAGE) * STAGE;
-        if constexpr (XT == 1) {
+        if constexpr (PAIRED) {
             // k steps 0..3 = (pair 0, step 0), (pair 0, step 1), (pair 1, step 0), (pair 1, step 1).  The second
             // step of a pair reads the raw weights of the next pair and converts their first half (whose
             // registers the first step has finished with) under its own MFMAs; the first step of the next
@@ -767,7 +786,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
                         o[e] = (half_t)f[e];
                     }
                     if (QOUT == 0 || out != nullptr) *reinterpret_cast<half4 *>(ot + lr * OROW + nl * 2) = o;
-                    if constexpr (!PLAIN && XT == 0) {
+                    if constexpr (!PLAIN && !A16) {
                         if (acc_out != nullptr) {
                             const int m = mw + fm * 32 + lr;
                             if (m < M && nw + nl < N)
@@ -1077,9 +1096,13 @@ hipError_t launch_gemm_tile(const GemmArgs &a, int block, hipStream_t st) {
     }
     // INT8 weights: two K teams of 2 x 2 waves (wave tile 64 x 64); measured 5-8 % ahead of eight waves side by
     // side on 4096x1024x4096 and 2048x2048x8192, level on 2048x2048x2048.  INT4 weights measured 2-3 % slower with
-    // teams (the nibble unpack already fills the stage boundary) and keep the 2 x 4 layout.
+    // teams (the nibble unpack already fills the stage boundary) and keep the 2 x 4 layout, with the nibbles
+    // packed in LDS (XT = 3): these tiles wait for their operand loads, and half the weight bytes measured
+    // 5-14 % faster (2048x2048x2048 13.5 -> 12.8 us, 4096x1024x4096 27.1 -> 23.7 us).  On 256 x 256 tiles, which
+    // run at the chip's power limit, the register-side unpack measured 5 % slower than unpacking on the way
+    // into LDS (4096x16384x4096 233 -> 245 us), so they keep that.
     if (a.w_bits == 8) return launch_tile_t<128, 128, 2, 2, 128, 4, 8, 0, 0, 0, 2>(a, st);
-    return launch_tile_t<128, 128, 2, 4, 128, 4, 4>(a, st);
+    return launch_tile_t<128, 128, 2, 4, 128, 4, 4, 3>(a, st);
 }
 
 // The 128x128-tile schedule with K split over workgroups and a second kernel for the epilogue: for
@@ -1117,8 +1140,10 @@ hipError_t launch_gemm_tile_splitk(const GemmArgs &a, hipStream_t st) {
     if (ks < 2 || a.workspace == nullptr ||
         a.workspace_bytes < kWsFixedBytes + (size_t)ks * a.M * a.N * sizeof(int32_t))
         return hipErrorInvalidValue;
+    // INT4 weights packed in LDS (XT = 3), as in the unsplit 128 x 128 schedule: 4096x16384 at 256 / 512 tokens
+    // 38.6 -> 35.3 / 56.4 -> 52.0 us
     hipError_t e = (a.w_bits == 8) ? launch_tile_t<128, 128, 2, 4, 128, 4, 8, 0, 0, 1>(a, st, ks)
-                                   : launch_tile_t<128, 128, 2, 4, 128, 4, 4, 0, 0, 1>(a, st, ks);
+                                   : launch_tile_t<128, 128, 2, 4, 128, 4, 4, 3, 0, 1>(a, st, ks);
     if (e != hipSuccess) return e;
     return launch_splitk_finish<0>(a, ks, st);
 }
