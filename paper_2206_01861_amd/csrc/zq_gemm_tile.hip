@@ -146,7 +146,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // become FP16 in registers after the fragment read: one 16-byte read holds the weights of two k
     // steps, converted exactly by cvt8_i8_f16.  So that a lane's sixteen weights meet the right
     // activations, the k steps of a stage take the activation chunks in a permuted order (see
-    // read_x_a16): a sum over K does not depend on the order of K.
+    // read_x_paired): a sum over K does not depend on the order of K.
     // XT = 2: the weights take the register path of the INT4 weights (16 source bytes -> two 16-byte
     // chunks) with the same conversion instead of the nibble unpack, and sit in LDS as FP16.
     // XT = 3: INT8 activations, INT4 weights packed in LDS (again BK/2 bytes of a weight row per stage):
@@ -395,40 +395,40 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     // last eight the second.  The activations of the same values of K are chunk 4*pair + 2*lc + t for step
     // t of the pair, so every step reads one 16-byte activation chunk per row as before.
     const int sww = swz<BKW>(lr);
-    auto read_x_a16 = [&](const uint8_t *sb, int ks, int32x4(&bx)[FM]) {
+    auto read_x_paired = [&](const uint8_t *sb, int ks, int32x4(&bx)[FM]) {
         const int p = (((ks / 2) * 4 + 2 * lc + (ks & 1)) ^ sw) * 16;
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) bx[fm] = *reinterpret_cast<const int32x4 *>(sb + x_off + fm * 32 * BK + p);
     };
     int32x4 w_raw[FN];                       // the narrow weights of the next pair of k steps
     using WOp = typename std::conditional<A16, half8, int32x4>::type;
-    WOp w_f16[2][FN];                        // [step of the pair][fragment]: one set, rewritten once the
+    WOp w_op[2][FN];                        // [step of the pair][fragment]: one set, rewritten once the
                                              // second step's MFMAs have been issued (register budget)
-    auto read_w_a16 = [&](const uint8_t *sb, int pair) {
+    auto read_w_paired = [&](const uint8_t *sb, int pair) {
         const int p = ((pair * 2 + lc) ^ sww) * 16;
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn) w_raw[fn] = *reinterpret_cast<const int32x4 *>(sb + w_off + fn * 32 * BKW + p);
     };
     // first (T = 0) or last (T = 1) eight bytes of w_raw -> the operands of that step of the pair (eight INT8
     // codes to FP16, or sixteen nibbles to INT8 times 16, both exact)
-    auto convert_w_a16 = [&](auto t_c) __attribute__((always_inline)) {
+    auto convert_w_paired = [&](auto t_c) __attribute__((always_inline)) {
         constexpr int T = decltype(t_c)::value;
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
             if constexpr (A16) {
-                w_f16[T][fn] = cvt8_i8_f16((uint32_t)w_raw[fn][2 * T], (uint32_t)w_raw[fn][2 * T + 1]);
+                w_op[T][fn] = cvt8_i8_f16((uint32_t)w_raw[fn][2 * T], (uint32_t)w_raw[fn][2 * T + 1]);
             } else {
                 uint32_t d0, d1, d2, d3;
                 unpack8_nat((uint32_t)w_raw[fn][2 * T], d0, d1);
                 unpack8_nat((uint32_t)w_raw[fn][2 * T + 1], d2, d3);
-                w_f16[T][fn] = int32x4{(int)d0, (int)d1, (int)d2, (int)d3};
+                w_op[T][fn] = int32x4{(int)d0, (int)d1, (int)d2, (int)d3};
             }
     };
     using T0 = std::integral_constant<int, 0>;
     using T1 = std::integral_constant<int, 1>;
     // order of issue inside a step: one LDS read per MFMA while reads are left, then the conversion
     // spread over the remaining MFMAs
-    auto pace_a16 = [&](auto reads_c) __attribute__((always_inline)) {
+    auto pace_paired = [&](auto reads_c) __attribute__((always_inline)) {
         constexpr int READS = decltype(reads_c)::value;
         constexpr int NM = FN * FM;
         constexpr int VC = 10 * FN;                // VALU instructions of one conversion
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
     };
     using RX = std::integral_constant<int, FM>;          // a step that reads activation fragments only
     using RXW = std::integral_constant<int, FM + FN>;    // ... and the raw weights of the next pair
-    auto mfma_step_a16 = [&](const WOp(&a)[FN], const int32x4(&bx)[FM]) {
+    auto mfma_step_paired = [&](const WOp(&a)[FN], const int32x4(&bx)[FM]) {
         if constexpr (PAIRED) {
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn)
@@ -522,10 +522,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
         wait_vmcnt<0>();
     __syncthreads();
     if constexpr (PAIRED) {
-        read_x_a16(smem, 0, b0);
-        read_w_a16(smem, 0);
-        convert_w_a16(T0{});
-        convert_w_a16(T1{});
+        read_x_paired(smem, 0, b0);
+        read_w_paired(smem, 0);
+        convert_w_paired(T0{});
+        convert_w_paired(T1{});
     } else {
         read_frags(smem, 0, a0, b0);
     }
@@ -544,30 +544,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KT, (WAVES_M * WAVES_N * K
             // step of a pair reads the raw weights of the next pair and converts their first half (whose
             // registers the first step has finished with) under its own MFMAs; the first step of the next
             // pair converts the second half under its MFMAs.  One set of converted operands is enough.
-            read_x_a16(sb, 1, b1);
-            mfma_step_a16(w_f16[0], b0);
-            convert_w_a16(T1{});
-            pace_a16(RX{});
-            read_x_a16(sb, 2, b0);
-            read_w_a16(sb, 1);
-            mfma_step_a16(w_f16[1], b1);
-            convert_w_a16(T0{});
-            pace_a16(RXW{});
-            read_x_a16(sb, 3, b1);
-            mfma_step_a16(w_f16[0], b0);
-            convert_w_a16(T1{});
-            pace_a16(RX{});
+            read_x_paired(sb, 1, b1);
+            mfma_step_paired(w_op[0], b0);
+            convert_w_paired(T1{});
+            pace_paired(RX{});
+            read_x_paired(sb, 2, b0);
+            read_w_paired(sb, 1);
+            mfma_step_paired(w_op[1], b1);
+            convert_w_paired(T0{});
+            pace_paired(RXW{});
+            read_x_paired(sb, 3, b1);
+            mfma_step_paired(w_op[0], b0);
+            convert_w_paired(T1{});
+            pace_paired(RX{});
             if constexpr (!LAST) {
                 wait_vmcnt<(NSTAGE - 2) * LPS>();         // stage kt+1 has landed
                 lds_barrier();
                 issue_direct(kt0 + kt + NSTAGE, kt % NSTAGE, kt + NSTAGE >= n_loc);
-                read_x_a16(sn, 0, b0);
-                read_w_a16(sn, 0);
+                read_x_paired(sn, 0, b0);
+                read_w_paired(sn, 0);
             }
-            mfma_step_a16(w_f16[1], b1);
+            mfma_step_paired(w_op[1], b1);
             if constexpr (!LAST) {
-                convert_w_a16(T0{});
-                pace_a16(RXW{});
+                convert_w_paired(T0{});
+                pace_paired(RXW{});
             }
             return;
         }
