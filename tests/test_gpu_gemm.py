@@ -62,6 +62,10 @@ def _check(orc, res, xq, s_tok, codes, s_w, bias, what):
 
 
 # (variant, M, N, K, groups): several tiles in each direction plus ragged tails
+# Every shape runs with INT8 and with INT4 weights.  With INT4 weights the TILE128 and TILE_SPLITK cases take the kernel that keeps
+# the nibbles packed in LDS and unpacks them after the fragment read (its k steps visit K in a permuted order, so
+# the K tails of 32, 96, 544, 800 and 4000 below are the cases that matter for it); the other tiled cases unpack on
+# the way into LDS.
 SHAPES = [
     (SIMPLE, 1, 16, 16, 1), (SIMPLE, 7, 48, 80, 3), (SIMPLE, 17, 768, 784, 48), (SIMPLE, 129, 96, 1024, 2),
     (TILE128, 128, 768, 768, 48), (TILE128, 129, 272, 256, 17), (TILE128, 300, 400, 384, 25),
